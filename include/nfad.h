@@ -1,0 +1,111 @@
+/*
+ * nfad.h -- C ABI of libnfad: nested forward-mode automatic differentiation for
+ * element-wise activation functions on AMD MI355X (gfx950).
+ *
+ * The method (Sec. II-C eq. 3-4, Sec. II-E of "Nesting Forward Automatic
+ * Differentiation for Memory-Efficient Deep Neural Network Training"): during the
+ * forward pass each element carries the dual number (x, 1) through the activation,
+ * which yields y = f(x) and the local derivative dydx = f'(x) together.  Only dydx
+ * is kept for the backward pass, which is then one multiply, gx = gy * dydx.
+ * The two alternatives the paper compares against are exported beside it:
+ * ordinary back-propagation that saves every intermediate (Sec. II-C eqs. 1-2) and
+ * recomputation from x in the backward pass (Sec. II-C, "Recomputation").
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ * Pointers  : DEVICE pointers (HIP global memory) to flat, contiguous arrays of `n`
+ *             elements of `dtype`.  All tensors of one call share `dtype`.  Tensor
+ *             shape (NCHW, row-major, ...) is irrelevant: the operation is
+ *             element-wise.  `saved` is a HOST array of device pointers.
+ * Ownership : the caller owns every buffer.  The library never allocates, frees or
+ *             keeps a pointer, and has no state (thread-safe, re-entrant).
+ * Stream    : `stream` is a hipStream_t passed as void*; NULL is the default stream.
+ *             Calls enqueue work and return; they never synchronise.
+ * Math      : fp32 internally for all dtypes; fp16/bf16 results are rounded once,
+ *             to nearest even, on store.  Swish uses beta = 1 (Table I).
+ * Alignment : pointers must be aligned to the element size (else NFAD_EALIGN).
+ *             If every pointer of a call is 16-byte aligned the 128-bit vector body
+ *             runs; otherwise a scalar kernel produces the same values.
+ * Aliasing  : an output may coincide EXACTLY with an input of the same call
+ *             (y == x, gx == gy, gx == dydx, gx == saved[j]); two outputs must not
+ *             coincide (NFAD_EALIAS).  Partial overlap is undefined.
+ * Errors    : every call returns an nfad_status_t as int.  Arguments are validated
+ *             on the host before any HIP call; n == 0 returns NFAD_OK without a
+ *             launch (pointers may then be NULL).  A failed launch gives NFAD_ELAUNCH.
+ *             Nothing throws or aborts across this boundary.
+ * Finite x  : for every finite input the results are finite: y -> x, dydx -> 1 as
+ *             x -> +inf and y -> -0, dydx -> -0 as x -> -inf.
+ */
+#ifndef NFAD_H_
+#define NFAD_H_
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Activations: Table I (GELU tanh form, Swish, Mish); the erf form of GELU is the
+ * textbook x*Phi(x). */
+typedef enum {
+  NFAD_GELU_TANH = 0, /* 0.5 x (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3))) */
+  NFAD_GELU_ERF = 1,  /* 0.5 x (1 + erf(x / sqrt 2))                      */
+  NFAD_SWISH = 2,     /* x * sigmoid(x)                                   */
+  NFAD_MISH = 3       /* x * tanh(ln(1 + e^x))                            */
+} nfad_kind_t;
+
+typedef enum { NFAD_F32 = 0, NFAD_F16 = 1, NFAD_BF16 = 2 } nfad_dtype_t;
+
+typedef enum {
+  NFAD_OK = 0,
+  NFAD_EINVAL_KIND = 1,
+  NFAD_EINVAL_DTYPE = 2,
+  NFAD_ENULL = 3,   /* a required pointer is NULL while n > 0            */
+  NFAD_EALIGN = 4,  /* a pointer is not aligned to the element size      */
+  NFAD_EALIAS = 5,  /* two outputs of one call coincide                  */
+  NFAD_ELAUNCH = 6  /* the HIP runtime refused the launch                */
+} nfad_status_t;
+
+#define NFAD_MAX_SAVED 4
+
+/* Forward pass of the method (Sec. II-C eq. 3): y[i] = f(x[i]), dydx[i] = f'(x[i]).
+ * x: in, n elements.  y, dydx: out, n elements each.  dydx is the only tensor the
+ * caller needs to keep for nfad_bwd; x may be released afterwards. */
+int nfad_fwd(int kind, const void* x, void* y, void* dydx, size_t n, int dtype, void* stream);
+
+/* Backward pass of the method (Sec. II-C eq. 4, Sec. II-E): gx[i] = gy[i] * dydx[i].
+ * gy: upstream gradient, in.  dydx: as written by nfad_fwd, in.  gx: out. */
+int nfad_bwd(const void* gy, const void* dydx, void* gx, size_t n, int dtype, void* stream);
+
+/* Recomputation baseline (Sec. II-C, "Recomputation"): forward writes y only and the
+ * caller keeps x; backward re-derives f'(x) and writes gx[i] = gy[i] * f'(x[i]). */
+int nfad_recompute_fwd(int kind, const void* x, void* y, size_t n, int dtype, void* stream);
+int nfad_recompute_bwd(int kind, const void* gy, const void* x, void* gx, size_t n, int dtype,
+                       void* stream);
+
+/* Save-all baseline (Sec. II-C eqs. 1-2): ordinary back-propagation through the
+ * activation's primitive operations, keeping what each primitive's backward needs:
+ *   Swish     k = 2: saved = { x, s = sigmoid(x) }
+ *   Mish      k = 2: saved = { x, t = tanh(softplus(x)) }
+ *   GELU-erf  k = 3: saved = { x, h = 0.5 x, s = 1 + erf(x / sqrt 2) }
+ *   GELU-tanh k = 4: saved = { x, t = tanh(u), h = 0.5 x, s = 1 + t }
+ * nfad_saveall_num_saved returns k (or -1 for a bad kind).
+ * `saved` is a host array of k device pointers.  saved[0] stands for x, which already
+ * exists: the forward pass never writes it (it may be NULL there) and writes
+ * saved[1..k-1]; the backward pass reads gy and all k tensors (saved[0] = x). */
+int nfad_saveall_num_saved(int kind);
+int nfad_saveall_fwd(int kind, const void* x, void* y, void* const* saved, size_t n, int dtype,
+                     void* stream);
+int nfad_saveall_bwd(int kind, const void* gy, const void* const* saved, void* gx, size_t n,
+                     int dtype, void* stream);
+
+/* Static, NUL-terminated description of a status code (never NULL). */
+const char* nfad_status_string(int status);
+
+/* major * 10000 + minor * 100 + patch */
+int nfad_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NFAD_H_ */

@@ -1,0 +1,57 @@
+"""Tolerance and comparison helpers shared by the parity tests (no method arithmetic here).
+
+Bar (fp32 math, one rounding to storage):
+  f32 storage : |gpu - ref| <= max(2e-6, ulp_f32(ref))      (2e-6 flat wherever |ref| < 16)
+  f16 / bf16  : |gpu - ref| <= max(ulp_T(ref), 2e-6)
+with ulp_T(v) = 2^(max(floor(log2 |v|), e_min) - p), (p, e_min) = (23,-126) f32, (10,-14) f16,
+(7,-126) bf16, and ref the fp64 oracle value on the storage-rounded input.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+P_EMIN = {torch.float32: (23, -126), torch.float16: (10, -14), torch.bfloat16: (7, -126)}
+ABS_FLOOR = 2e-6
+
+
+def ulp_of(ref: torch.Tensor, dtype: torch.dtype) -> torch.Tensor:
+    """ulp of `dtype` at the magnitude of the float64 tensor `ref`."""
+    p, emin = P_EMIN[dtype]
+    _, e = torch.frexp(ref.abs())           # |ref| = m * 2^e, m in [0.5, 1)
+    e = torch.clamp(e.to(torch.int32) - 1, min=emin)
+    e = torch.where(ref == 0, torch.full_like(e, emin), e)
+    return torch.ldexp(torch.ones_like(ref), e - p)
+
+
+def tolerance(ref: torch.Tensor, dtype: torch.dtype) -> torch.Tensor:
+    return torch.clamp(ulp_of(ref, dtype), min=ABS_FLOOR)
+
+
+def compare(got: torch.Tensor, ref64, dtype: torch.dtype, what: str = "", flat_abs: float | None = None):
+    """Element-by-element check of a storage tensor against float64 reference values.
+    Returns a dict of statistics; raises AssertionError naming the worst element."""
+    dev = got.device
+    ref = torch.as_tensor(np.asarray(ref64), dtype=torch.float64).reshape(-1).to(dev)
+    g = got.detach().reshape(-1).to(torch.float64)
+    assert g.numel() == ref.numel(), (what, g.numel(), ref.numel())
+    if g.numel() == 0:
+        return {"n": 0, "max_abs": 0.0, "max_ulp": 0.0, "n_over_1ulp": 0}
+    finite = torch.isfinite(g)
+    assert bool(finite.all()), f"{what}: {int((~finite).sum())} non-finite outputs"
+    err = (g - ref).abs()
+    tol = tolerance(ref, dtype) if flat_abs is None else torch.full_like(ref, flat_abs)
+    bad = err > tol
+    ulps = err / ulp_of(ref, dtype)
+    stats = {
+        "n": int(g.numel()),
+        "max_abs": float(err.max()),
+        "max_ulp": float(ulps.max()),                 # strict statistic, reported not gated
+        "n_over_1ulp": int((ulps > 1.0).sum()),
+    }
+    if bool(bad.any()):
+        i = int(torch.argmax(err / tol))
+        raise AssertionError(
+            f"{what}: {int(bad.sum())}/{g.numel()} elements out of tolerance; worst at {i}: "
+            f"got {float(g[i])!r} ref {float(ref[i])!r} err {float(err[i]):.3e} tol {float(tol[i]):.3e}")
+    return stats

@@ -1,0 +1,103 @@
+"""Host-only checks of the C ABI: the library loads without a GPU, exports every symbol the
+header declares, and rejects bad arguments before touching the HIP runtime."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2209_10778_amd as nfad
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "nfad.h")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(nfad_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_declares_the_expected_entry_points():
+    assert declared_functions() == sorted([
+        "nfad_fwd", "nfad_bwd", "nfad_recompute_fwd", "nfad_recompute_bwd", "nfad_saveall_num_saved",
+        "nfad_saveall_fwd", "nfad_saveall_bwd", "nfad_status_string", "nfad_version"])
+
+
+def test_library_exports_every_declared_symbol():
+    L = ctypes.CDLL(nfad.lib_path())
+    for name in declared_functions():
+        assert hasattr(L, name), f"libnfad.so does not export {name}"
+
+
+def test_version_and_status_strings():
+    assert nfad.nfad_version() >= 100
+    seen = {nfad.nfad_status_string(s) for s in range(7)}
+    assert len(seen) == 7 and all(seen)
+    assert nfad.nfad_status_string(0) == "ok"
+    assert nfad.nfad_status_string(12345) == "unknown status"
+
+
+def test_num_saved():
+    assert [nfad.nfad_saveall_num_saved(k) for k in nfad.KINDS] == [4, 3, 2, 2]
+    assert nfad.nfad_saveall_num_saved(9) == -1
+
+
+def test_argument_validation_precedes_any_launch():
+    L = nfad.lib()
+    A = 1 << 20           # fake, suitably aligned addresses: validation never dereferences them
+    OK, EKIND, EDTYPE, ENULL, EALIGN, EALIAS = 0, 1, 2, 3, 4, 5
+    assert L.nfad_fwd(4, A, A + 64, A + 128, 8, 0, None) == EKIND
+    assert L.nfad_fwd(-1, A, A + 64, A + 128, 8, 0, None) == EKIND
+    assert L.nfad_fwd(0, A, A + 64, A + 128, 8, 3, None) == EDTYPE
+    assert L.nfad_fwd(0, None, A + 64, A + 128, 8, 0, None) == ENULL
+    assert L.nfad_fwd(0, A, None, A + 128, 8, 0, None) == ENULL
+    assert L.nfad_fwd(0, A, A + 64, None, 8, 0, None) == ENULL
+    assert L.nfad_fwd(0, A + 2, A + 64, A + 128, 8, 0, None) == EALIGN    # fp32 needs 4-byte alignment
+    assert L.nfad_fwd(0, A + 1, A + 64, A + 128, 8, 2, None) == EALIGN    # bf16 needs 2-byte alignment
+    assert L.nfad_fwd(0, A, A + 64, A + 64, 8, 0, None) == EALIAS
+    assert L.nfad_fwd(0, None, None, None, 0, 0, None) == OK               # n == 0: nothing to do
+    assert L.nfad_fwd(0, None, None, None, 0, 9, None) == EDTYPE           # but dtype is still checked
+    assert L.nfad_bwd(None, A, A, 4, 1, None) == ENULL
+    assert L.nfad_bwd(A, A, A + 1, 4, 1, None) == EALIGN
+    assert L.nfad_bwd(None, None, None, 0, 1, None) == OK
+    assert L.nfad_recompute_fwd(7, A, A, 4, 0, None) == EKIND
+    assert L.nfad_recompute_fwd(2, A, None, 4, 0, None) == ENULL
+    assert L.nfad_recompute_bwd(2, A, None, A, 4, 0, None) == ENULL
+    assert L.nfad_recompute_bwd(2, A, A, A, 4, 5, None) == EDTYPE
+    vpp = ctypes.c_void_p * 4
+    assert L.nfad_saveall_fwd(2, A, A + 64, None, 4, 0, None) == ENULL
+    assert L.nfad_saveall_fwd(2, A, A + 64, vpp(None, None, None, None), 4, 0, None) == ENULL
+    assert L.nfad_saveall_fwd(0, A, A + 64, vpp(None, A + 128, A + 192, A + 128), 4, 0, None) == EALIAS
+    assert L.nfad_saveall_fwd(5, A, A + 64, vpp(A, A, A, A), 4, 0, None) == EKIND
+    assert L.nfad_saveall_bwd(1, A, vpp(A, A, None, None), A, 4, 0, None) == ENULL
+    assert L.nfad_saveall_bwd(1, A, None, A, 0, 0, None) == OK
+
+
+def test_binding_rejects_host_tensors_and_mismatches():
+    import torch
+    x = torch.zeros(8)
+    with pytest.raises(ValueError):
+        nfad.nfad_fwd(nfad.SWISH, x, x.clone(), x.clone())
+    with pytest.raises(TypeError):
+        nfad.nfad_fwd(nfad.SWISH, x.double(), x.double(), x.double())
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    from paper_2209_10778_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", "/nonexistent/libnfad.so")
+    with pytest.raises(ImportError):
+        binding.lib()
+
+
+def test_product_path_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2209_10778_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".inc", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text, f
+                assert "nfad_oracle" not in text, f
+    otext = open(os.path.join(ROOT, "oracle", "__init__.py")).read() + open(os.path.join(ROOT, "oracle", "nfad_oracle.c")).read()
+    assert "paper_2209_10778_amd" not in otext

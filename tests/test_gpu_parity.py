@@ -1,0 +1,314 @@
+"""GPU parity: every libnfad entry point against the fp64 oracle, element by element, on the
+same seeded storage-rounded inputs, called through the C ABI (ctypes binding).
+
+No expected value and no oracle input comes from the GPU: backward-pass inputs (dydx, the
+saved intermediates) are the ORACLE's forward results rounded to storage, fed to both sides.
+"""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2209_10778_amd as nfad
+from paper_2209_10778_amd import inputs
+from parity import compare
+
+pytestmark = pytest.mark.gpu
+
+DTYPES = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+DEV = "cuda:0"
+
+# sizes: several 16-byte-vector tiles plus a partial tile plus a scalar tail, for every dtype
+# (one tile = 256 lanes * unroll * 4 or 8 elements <= 8192 elements)
+N_RAGGED = 5 * 8192 + 3 * 256 * 8 + 777 + 3
+
+
+def stress_x(n, seed, dtype):
+    """N(0,3) with 1% outliers in +-[20,80] plus hand-picked special values."""
+    a = inputs.gaussian(n, 3.0, seed)
+    inputs.add_outliers(a, seed + 2, seed + 3, seed + 4)
+    special = np.array([0.0, -0.0, 1e-30, -1e-30, 1e-6, -1e-6, 80.0, -80.0, 20.0, -20.0, 6.0, -6.0,
+                        -0.7524614, -0.7517915, -1.2784645, -1.1924312, 128.0, -128.0, 13.0, -13.0,
+                        0.5, -0.5, 1.0, -1.0, 2.0, -2.0, 4.0, -4.0, 8.0, -8.0, 16.0, -16.0], np.float32)
+    k = min(n, special.size)
+    a[:k] = special[:k]
+    return inputs.to_storage(a, dtype)
+
+
+def dev(t):
+    return t.to(DEV)
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _lib_loaded():
+    assert torch.cuda.is_available()
+    nfad.lib()          # fails loudly if libnfad.so is missing: there is no fallback
+    yield
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ the method: fwd and bwd
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("kind", nfad.KINDS)
+def test_fwd_matches_oracle(kind, dtype):
+    td = DTYPES[dtype]
+    x = stress_x(N_RAGGED, 1000 + kind, dtype)
+    y_ref, d_ref = oracle.fwd(kind, inputs.storage_to_f64(x))
+    xd = dev(x)
+    y = torch.full_like(xd, float("nan"))
+    d = torch.full_like(xd, float("nan"))
+    nfad.nfad_fwd(kind, xd, y, d)
+    torch.cuda.synchronize()
+    sy = compare(y, y_ref, td, f"fwd y kind={kind} {dtype}")
+    sd = compare(d, d_ref, td, f"fwd dydx kind={kind} {dtype}")
+    print(f"\n[fwd {nfad.KIND_NAMES[kind]} {dtype}] y {sy}  dydx {sd}")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_fwd_gaussian_inputs_flat_2e6(dtype):
+    """Unit-variance inputs (|x| < 6): the flat max-abs 2e-6 bar for fp32 storage, and the
+    1-ulp bar for 16-bit storage."""
+    td = DTYPES[dtype]
+    for kind in nfad.KINDS:
+        x = inputs.to_storage(inputs.gaussian(N_RAGGED, 1.0, 2000 + kind), dtype)
+        y_ref, d_ref = oracle.fwd(kind, inputs.storage_to_f64(x))
+        xd = dev(x)
+        y, d = torch.empty_like(xd), torch.empty_like(xd)
+        nfad.nfad_fwd(kind, xd, y, d)
+        flat = 2e-6 if dtype == "f32" else None
+        compare(y, y_ref, td, f"y kind={kind}", flat_abs=flat)
+        compare(d, d_ref, td, f"dydx kind={kind}", flat_abs=flat)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_bwd_matches_oracle(dtype):
+    td = DTYPES[dtype]
+    kind = nfad.MISH
+    x = stress_x(N_RAGGED, 3000, dtype)
+    _, d_ref = oracle.fwd(kind, inputs.storage_to_f64(x))
+    dydx = inputs.to_storage(d_ref.astype(np.float32), dtype)          # oracle's derivative, stored
+    gy = inputs.to_storage(inputs.gaussian(N_RAGGED, 0.1, 3001), dtype)
+    gx_ref = oracle.bwd(inputs.storage_to_f64(gy), inputs.storage_to_f64(dydx))
+    gx = torch.full((N_RAGGED,), float("nan"), dtype=td, device=DEV)
+    nfad.nfad_bwd(dev(gy), dev(dydx), gx)
+    st = compare(gx, gx_ref, td, f"bwd {dtype}")
+    if dtype != "f32":
+        # the product of two <= 11-bit significands is exact in fp32: one rounding only
+        assert st["max_ulp"] <= 0.5 + 1e-9 or st["max_abs"] <= 2e-6
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("kind", nfad.KINDS)
+def test_fwd_then_bwd_end_to_end(kind, dtype):
+    """GPU fwd feeding GPU bwd against gy * f'(x) from the oracle: two roundings of storage."""
+    td = DTYPES[dtype]
+    x = inputs.to_storage(inputs.gaussian(N_RAGGED, 1.5, 3100 + kind), dtype)
+    gy = inputs.to_storage(inputs.gaussian(N_RAGGED, 1.0, 3200 + kind), dtype)
+    _, d_ref = oracle.fwd(kind, inputs.storage_to_f64(x))
+    gx_ref = oracle.bwd(inputs.storage_to_f64(gy), d_ref)
+    xd, gyd = dev(x), dev(gy)
+    y, d, gx = torch.empty_like(xd), torch.empty_like(xd), torch.empty_like(xd)
+    nfad.nfad_fwd(kind, xd, y, d)
+    nfad.nfad_bwd(gyd, d, gx)
+    g = gx.double().cpu().numpy()
+    # error budget: dydx is off by <= 1 ulp_T(dydx) (or 2e-6), scaled by |gy|, plus the final rounding
+    from parity import tolerance
+    tol_d = tolerance(torch.from_numpy(d_ref), td).numpy()
+    tol_g = tolerance(torch.from_numpy(gx_ref), td).numpy()
+    assert np.all(np.abs(g - gx_ref) <= np.abs(inputs.storage_to_f64(gy)) * tol_d + tol_g)
+
+
+# ------------------------------------------------------------------ baselines
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("kind", nfad.KINDS)
+def test_recompute_matches_oracle(kind, dtype):
+    td = DTYPES[dtype]
+    x = stress_x(N_RAGGED, 4000 + kind, dtype)
+    gy = inputs.to_storage(inputs.gaussian(N_RAGGED, 0.1, 4100 + kind), dtype)
+    x64, gy64 = inputs.storage_to_f64(x), inputs.storage_to_f64(gy)
+    xd = dev(x)
+    y, gx = torch.empty_like(xd), torch.empty_like(xd)
+    nfad.nfad_recompute_fwd(kind, xd, y)
+    nfad.nfad_recompute_bwd(kind, dev(gy), xd, gx)
+    compare(y, oracle.recompute_fwd(kind, x64), td, f"recompute fwd kind={kind} {dtype}")
+    # gx = gy * f'(x): the fp32 derivative is within tolerance(d) of exact, scaled by |gy|
+    gx_ref = oracle.recompute_bwd(kind, gy64, x64)
+    _, d_ref = oracle.fwd(kind, x64)
+    from parity import tolerance
+    tol = np.abs(gy64) * np.maximum(tolerance(torch.from_numpy(d_ref), torch.float32).numpy(), 2e-6) \
+        + tolerance(torch.from_numpy(gx_ref), td).numpy()
+    assert np.all(np.abs(gx.double().cpu().numpy() - gx_ref) <= tol)
+    assert bool(torch.isfinite(gx.float()).all())
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("kind", nfad.KINDS)
+def test_saveall_matches_oracle(kind, dtype):
+    td = DTYPES[dtype]
+    k = nfad.nfad_saveall_num_saved(kind)
+    assert k == oracle.num_saved(kind)
+    x = stress_x(N_RAGGED, 5000 + kind, dtype)
+    gy = inputs.to_storage(inputs.gaussian(N_RAGGED, 0.1, 5100 + kind), dtype)
+    x64 = inputs.storage_to_f64(x)
+    y_ref, saved_ref = oracle.saveall_fwd(kind, x64)
+    xd = dev(x)
+    y = torch.empty_like(xd)
+    saved = [xd] + [torch.full_like(xd, float("nan")) for _ in range(k - 1)]
+    nfad.nfad_saveall_fwd(kind, xd, y, saved)
+    compare(y, y_ref, td, f"saveall fwd y kind={kind} {dtype}")
+    for j in range(1, k):
+        compare(saved[j], saved_ref[j], td, f"saveall fwd saved[{j}] kind={kind} {dtype}")
+    # backward on the ORACLE's intermediates rounded to storage, fed to both sides
+    saved_st = [x] + [inputs.to_storage(s.astype(np.float32), dtype) for s in saved_ref[1:]]
+    gx_ref = oracle.saveall_bwd(kind, inputs.storage_to_f64(gy), [inputs.storage_to_f64(s) for s in saved_st])
+    gx = torch.empty_like(xd)
+    nfad.nfad_saveall_bwd(kind, dev(gy), [dev(s) for s in saved_st], gx)
+    # fp32 evaluation of a sum of products: a few fp32 ulps of the largest term, then one rounding
+    from parity import tolerance
+    gy64 = np.abs(inputs.storage_to_f64(gy))
+    slack = gy64 * 4e-6 * np.maximum(1.0, np.abs(x64))
+    tol = tolerance(torch.from_numpy(gx_ref), td).numpy() + slack
+    assert np.all(np.abs(gx.double().cpu().numpy() - gx_ref) <= tol)
+
+
+# ------------------------------------------------------------------ exhaustive 16-bit inputs
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_every_16bit_pattern(dtype):
+    td = DTYPES[dtype]
+    bits = torch.arange(65536, dtype=torch.int32).to(torch.int16)
+    x = bits.view(td)
+    xf = x.to(torch.float64)
+    gate = torch.isfinite(xf) & (xf.abs() <= 128.0)
+    xg = x[gate].contiguous()
+    x64 = inputs.storage_to_f64(xg)
+    xd = dev(xg)
+    report = {}
+    for kind in nfad.KINDS:
+        y, d = torch.empty_like(xd), torch.empty_like(xd)
+        nfad.nfad_fwd(kind, xd, y, d)
+        y_ref, d_ref = oracle.fwd(kind, x64)
+        sy = compare(y, y_ref, td, f"exhaustive y kind={kind} {dtype}")
+        sd = compare(d, d_ref, td, f"exhaustive dydx kind={kind} {dtype}")
+        report[nfad.KIND_NAMES[kind]] = (sy["max_ulp"], sy["n_over_1ulp"], sd["max_ulp"], sd["n_over_1ulp"])
+    # reported, not gated: finite inputs of larger magnitude must at least stay finite
+    big = x[torch.isfinite(xf) & (xf.abs() > 128.0)].contiguous()
+    bd = dev(big)
+    for kind in nfad.KINDS:
+        y, d = torch.empty_like(bd), torch.empty_like(bd)
+        nfad.nfad_fwd(kind, bd, y, d)
+        assert bool(torch.isfinite(d.float()).all()), f"non-finite dydx for large finite x, kind={kind}"
+        assert bool((~torch.isnan(y.float())).all())
+    print(f"\n[exhaustive {dtype}] strict-ulp report (max_ulp_y, n>1, max_ulp_d, n>1): {report}")
+
+
+# ------------------------------------------------------------------ edge cases
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_tiny_and_empty_sizes(dtype):
+    td = DTYPES[dtype]
+    kind = nfad.GELU_TANH
+    L = nfad.lib()
+    assert L.nfad_fwd(kind, None, None, None, 0, inputs_code(dtype), None) == 0
+    assert L.nfad_bwd(None, None, None, 0, inputs_code(dtype), None) == 0
+    for n in list(range(1, 20)) + [255, 256, 257, 2047, 2048, 2049]:
+        x = stress_x(n, 6000 + n, dtype)
+        y_ref, d_ref = oracle.fwd(kind, inputs.storage_to_f64(x))
+        # canaries either side catch out-of-bounds writes
+        pad = 64
+        buf_y = torch.full((n + 2 * pad,), 777.0, dtype=td, device=DEV)
+        buf_d = torch.full((n + 2 * pad,), 777.0, dtype=td, device=DEV)
+        xd = dev(x)
+        nfad.nfad_fwd(kind, xd, buf_y[pad:pad + n], buf_d[pad:pad + n])
+        compare(buf_y[pad:pad + n], y_ref, td, f"n={n} y")
+        compare(buf_d[pad:pad + n], d_ref, td, f"n={n} d")
+        for b in (buf_y, buf_d):
+            assert bool((b[:pad] == 777.0).all()) and bool((b[pad + n:] == 777.0).all()), f"n={n}: wrote out of bounds"
+
+
+def inputs_code(dtype):
+    return {"f32": nfad.F32, "f16": nfad.F16, "bf16": nfad.BF16}[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_misaligned_pointers_take_the_scalar_kernel(dtype):
+    td = DTYPES[dtype]
+    n = 10_000 + 5
+    for kind in (nfad.SWISH, nfad.GELU_ERF):
+        x = stress_x(n, 7000 + kind, dtype)
+        y_ref, d_ref = oracle.fwd(kind, inputs.storage_to_f64(x))
+        for off_x, off_y, off_d in ((1, 0, 0), (0, 1, 0), (0, 0, 3), (1, 2, 3)):
+            bx = torch.zeros(n + 8, dtype=td, device=DEV)
+            by = torch.full((n + 8,), 777.0, dtype=td, device=DEV)
+            bd = torch.full((n + 8,), 777.0, dtype=td, device=DEV)
+            bx[off_x:off_x + n] = dev(x)
+            nfad.nfad_fwd(kind, bx[off_x:off_x + n], by[off_y:off_y + n], bd[off_d:off_d + n])
+            compare(by[off_y:off_y + n], y_ref, td, f"misaligned y {off_x}{off_y}{off_d}")
+            compare(bd[off_d:off_d + n], d_ref, td, f"misaligned d {off_x}{off_y}{off_d}")
+            assert bool((by[:off_y] == 777.0).all()) and bool((by[off_y + n:] == 777.0).all())
+            assert bool((bd[:off_d] == 777.0).all()) and bool((bd[off_d + n:] == 777.0).all())
+
+
+def test_exact_aliasing_is_allowed():
+    td = torch.float32
+    n = N_RAGGED
+    kind = nfad.SWISH
+    x = stress_x(n, 8000, "f32")
+    y_ref, d_ref = oracle.fwd(kind, inputs.storage_to_f64(x))
+    xd = dev(x)
+    d = torch.empty_like(xd)
+    nfad.nfad_fwd(kind, xd, xd, d)            # in-place activation: y == x
+    compare(xd, y_ref, td, "in-place y")
+    compare(d, d_ref, td, "in-place dydx")
+    gy = inputs.to_storage(inputs.gaussian(n, 0.1, 8001), "f32")
+    dydx = inputs.to_storage(d_ref.astype(np.float32), "f32")
+    gx_ref = oracle.bwd(inputs.storage_to_f64(gy), inputs.storage_to_f64(dydx))
+    g1, d1 = dev(gy), dev(dydx)
+    nfad.nfad_bwd(g1, d1, g1)                 # gx == gy
+    compare(g1, gx_ref, td, "gx==gy")
+    g2, d2 = dev(gy), dev(dydx)
+    nfad.nfad_bwd(g2, d2, d2)                 # gx == dydx
+    compare(d2, gx_ref, td, "gx==dydx")
+    with pytest.raises(nfad.NfadError) as ei:
+        nfad.nfad_fwd(kind, xd, d, d)         # two outputs coincide
+    assert ei.value.status == 5
+
+
+def test_non_default_stream():
+    kind, dtype, td = nfad.MISH, "bf16", torch.bfloat16
+    x = stress_x(N_RAGGED, 9000, dtype)
+    y_ref, d_ref = oracle.fwd(kind, inputs.storage_to_f64(x))
+    xd = dev(x)
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    y, d = torch.empty_like(xd), torch.empty_like(xd)
+    with torch.cuda.stream(s):
+        nfad.nfad_fwd(kind, xd, y, d)          # binding picks up the current stream
+    nfad.nfad_fwd(kind, xd, y, d, stream=s)    # and an explicit one
+    s.synchronize()
+    compare(y, y_ref, td, "stream y")
+    compare(d, d_ref, td, "stream d")
+
+
+def test_beyond_32bit_element_count():
+    """n > 2^32 elements (bf16): 64-bit indexing.  The input is a short seeded pattern
+    repeated on the device; windows at the start, across 2^31 and 2^32, and at the ragged
+    end are checked against the oracle."""
+    td = torch.bfloat16
+    period = 1_000_003                       # odd prime: windows never align with tiles
+    n = (1 << 32) + (1 << 20) + 13
+    pat = stress_x(period, 9100, "bf16")
+    reps = n // period + 1
+    xd = dev(pat).repeat(reps)[:n].contiguous()
+    y, d = torch.empty_like(xd), torch.empty_like(xd)
+    kind = nfad.GELU_TANH
+    nfad.nfad_fwd(kind, xd, y, d)
+    torch.cuda.synchronize()
+    W = 50_000
+    for start in (0, (1 << 31) - W // 2, (1 << 32) - W // 2, n - W):
+        xs = xd[start:start + W].cpu()
+        y_ref, d_ref = oracle.fwd(kind, inputs.storage_to_f64(xs))
+        compare(y[start:start + W], y_ref, td, f"big y @{start}")
+        compare(d[start:start + W], d_ref, td, f"big d @{start}")
+    del xd, y, d
+    torch.cuda.empty_cache()
