@@ -1,0 +1,205 @@
+#!/usr/bin/env python3
+"""Benchmark of the libnfad hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic activations of the chosen
+configuration: the method's fused forward (y, dydx) and its backward gx = gy*dydx, then the
+two baselines the paper compares against (recomputation fwd/bwd, save-all fwd/bwd), each a
+single fused kernel.  Inputs are resident in HBM before the timed region starts.  Buffer
+sets are rotated so that successive launches do not hit in the 256 MB last-level cache.
+
+Prints ONE JSON line.  `value` is algorithmic HBM bytes of a step / step time.  `roofline`
+describes the method's forward kernel (nfad_fwd), its launch duration measured with events
+on the launch stream over a region of back-to-back launches.  `cpu_baseline` is the fp64
+oracle timed on the host cores on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=1, help="index into the benchmark configs (0..4)")
+    ap.add_argument("--tensor", type=int, default=0, help="which tensor of a multi-tensor config")
+    ap.add_argument("--kind", type=int, default=None, help="activation of a multi-activation config")
+    ap.add_argument("--dtype", type=str, default=None, help="dtype of a multi-dtype config")
+    ap.add_argument("--sets", type=int, default=0, help="rotating buffer sets (0 = enough for > 1 GiB)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy", type=int, default=0,
+                    help="also launch this many plain device copies of x (n elements read, n written): the "
+                         "known-size kernel that rocprofv3 FETCH_SIZE/WRITE_SIZE readings are scaled by")
+    ap.add_argument("--cpu-sample", type=int, default=1 << 25, help="max elements the oracle is timed on")
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (the path is element-wise and shards without "
+              "any exchange); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2209_10778_amd as nfad
+    from paper_2209_10778_amd import inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    nfad.lib()  # no fallback: raises if libnfad.so is missing
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    cfg = inputs.CONFIGS[args.config]
+    spec = cfg.tensors[args.tensor]
+    kind = cfg.kinds[0] if args.kind is None else args.kind
+    dtype = cfg.dtypes[0] if args.dtype is None else args.dtype
+    assert kind in cfg.kinds and dtype in cfg.dtypes
+    td = inputs.TORCH_DTYPE[dtype]
+    n = spec.n
+    es = 2 if dtype != "f32" else 4
+    k_saved = nfad.nfad_saveall_num_saved(kind)
+
+    # ---- inputs of record: seeded, storage-rounded on the host, then made resident
+    x_host = inputs.make_x(cfg, spec, dtype)
+    gy_host = inputs.make_gy(cfg, spec, dtype)
+    per_set_bytes = (5 + (k_saved - 1)) * n * es
+    nsets = args.sets or max(2, -(-(1 << 30) // per_set_bytes) + 1)
+    sets = []
+    for _ in range(nsets):
+        s = {"x": x_host.to(dev), "gy": gy_host.to(dev)}
+        for name in ("y", "dydx", "gx"):
+            s[name] = torch.empty(n, dtype=td, device=dev)
+        s["saved"] = [s["x"]] + [torch.empty(n, dtype=td, device=dev) for _ in range(k_saved - 1)]
+        sets.append(s)
+    stream = torch.cuda.current_stream()
+
+    kernels = {
+        "nfad_fwd": (lambda s: nfad.nfad_fwd(kind, s["x"], s["y"], s["dydx"], stream), 3),
+        "nfad_bwd": (lambda s: nfad.nfad_bwd(s["gy"], s["dydx"], s["gx"], stream), 3),
+        "recompute_fwd": (lambda s: nfad.nfad_recompute_fwd(kind, s["x"], s["y"], stream), 2),
+        "recompute_bwd": (lambda s: nfad.nfad_recompute_bwd(kind, s["gy"], s["x"], s["gx"], stream), 3),
+        "saveall_fwd": (lambda s: nfad.nfad_saveall_fwd(kind, s["x"], s["y"], s["saved"], stream), 1 + k_saved),
+        "saveall_bwd": (lambda s: nfad.nfad_saveall_bwd(kind, s["gy"], s["saved"], s["gx"], stream), 2 + k_saved),
+    }
+    words_per_step = sum(w for _, w in kernels.values())
+    bytes_per_step = words_per_step * n * es
+
+    def step(i):
+        s = sets[i % nsets]
+        for fn, _ in kernels.values():
+            fn(s)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = bytes_per_step / (ms_per_step * 1e-3) / 1e9
+
+    # ---- per-kernel launch duration: events on the launch stream around back-to-back launches
+    per_kernel = {}
+    for name, (fn, words) in kernels.items():
+        for i in range(max(3, args.warmup // 4)):
+            fn(sets[i % nsets])
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record(stream)
+        for i in range(args.steps):
+            fn(sets[i % nsets])
+        e1.record(stream)
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / args.steps
+        gbps = words * n * es / (us * 1e-6) / 1e9
+        per_kernel[name] = {"us": round(us, 2), "bytes_per_elem": words * es, "GB/s": round(gbps, 1),
+                            "frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4),
+                            "Gelem/s": round(n / (us * 1e-6) / 1e9, 1)}
+
+    for i in range(args.calib_copy):      # plain copy of known size, for counter calibration only
+        sets[i % nsets]["y"].copy_(sets[i % nsets]["x"])
+    torch.cuda.synchronize()
+
+    fwd = per_kernel["nfad_fwd"]
+    roofline = {"kernel": "nfad_fwd", "bound": "hbm", "achieved": fwd["GB/s"], "peak": HBM_PEAK_GBPS,
+                "unit": "GB/s", "frac": round(fwd["GB/s"] / HBM_PEAK_GBPS, 4), "traffic": None,
+                "algorithmic_bytes_per_launch": 3 * n * es, "avg_launch_us": fwd["us"]}
+    traffic_file = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "traffic.json")
+    if os.path.exists(traffic_file):  # HBM bytes per launch from committed rocprofv3 --pmc runs
+        try:
+            tr = json.load(open(traffic_file))
+            key = f"nfad_fwd/{nfad.KIND_NAMES[kind]}/{dtype}/{n}"
+            if key in tr:
+                roofline["traffic"] = tr[key]
+        except Exception:
+            pass
+
+    fad_us = per_kernel["nfad_fwd"]["us"] + per_kernel["nfad_bwd"]["us"]
+    rec_us = per_kernel["recompute_fwd"]["us"] + per_kernel["recompute_bwd"]["us"]
+    sav_us = per_kernel["saveall_fwd"]["us"] + per_kernel["saveall_bwd"]["us"]
+    summary = {
+        "fad_fwd_bwd_GB/s": round(6 * n * es / (fad_us * 1e-6) / 1e9, 1),
+        "fad_fwd_bwd_Gelem/s": round(n / (fad_us * 1e-6) / 1e9, 1),
+        "retained_bytes_per_elem": {"fad": es, "recompute": es, "saveall": k_saved * es},
+        "bytes_saved_per_elem_vs_saveall": (k_saved - 1) * es,
+        "time_fad_over_recompute": round(fad_us / rec_us, 4),
+        "time_fad_over_saveall": round(fad_us / sav_us, 4),
+        "bwd_time_fad_over_recompute": round(per_kernel["nfad_bwd"]["us"] / per_kernel["recompute_bwd"]["us"], 4),
+    }
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        import numpy as np
+        import oracle
+        ns = min(n, args.cpu_sample)
+        x64 = inputs.storage_to_f64(x_host[:ns])
+        gy64 = inputs.storage_to_f64(gy_host[:ns])
+        threads = oracle.max_threads()
+        oracle.fwd(kind, x64[: 1 << 16])          # warm the library, untimed
+        c0 = time.perf_counter()
+        y64, d64 = oracle.fwd(kind, x64)
+        oracle.bwd(gy64, d64)
+        oracle.recompute_fwd(kind, x64)
+        oracle.recompute_bwd(kind, gy64, x64)
+        _, saved64 = oracle.saveall_fwd(kind, x64)
+        oracle.saveall_bwd(kind, gy64, saved64)
+        c1 = time.perf_counter()
+        cpu_baseline = {
+            "value": round(words_per_step * ns * es / (c1 - c0) / 1e9, 3), "unit": "GB/s",
+            "cores": threads, "kind": "oracle",
+            "sample": f"first {ns} of {n} elements, one step (all six passes) in fp64 with OpenMP, "
+                      f"{c1 - c0:.2f} s wall; bytes counted as for the {dtype} GPU step",
+            "Gelem/s_per_pass": round(6 * ns / (c1 - c0) / 1e9, 4),
+        }
+        del y64, d64, saved64, x64, gy64
+
+    out = {
+        "metric": "achieved HBM GB/s (% of peak) for fused fwd+dydx and bwd; Gelem/s",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": dtype, "data": "synthetic",
+        "config": {"workload": cfg.name, "activation": nfad.KIND_NAMES[kind], "shape": list(spec.shape),
+                   "elements": n, "storage": dtype, "step": list(kernels.keys()),
+                   "bytes_per_step": bytes_per_step, "buffer_sets": nsets},
+        "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
+        "Gelem/s": round(6 * n / (ms_per_step * 1e-3) / 1e9, 1),
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "kernels": per_kernel, "summary": summary,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
