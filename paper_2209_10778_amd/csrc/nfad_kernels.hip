@@ -101,19 +101,23 @@ struct Storage<__bf16> {
 };
 
 // ------------------------------------------------------------------ per-element operations
-// An Op maps kIn input elements to kOut output elements, all fp32 in registers.
+// An Op maps kIn input elements to kOut output elements, all fp32 in registers.  kWide says
+// whether the results will be stored as fp32 (true) or rounded to fp16/bf16 (false); the
+// activations use it to pick their arithmetic tier, the other operations ignore it.
 
 // Forward pass of the method: (x) -> (y, dydx).                       Sec. II-C eq. 3
 template <int KIND>
 struct FwdOp {
   static constexpr int kIn = 1, kOut = 2;
+  template <bool kWide>
   __device__ __forceinline__ static void apply(const float (&in)[kIn], float (&out)[kOut]) {
-    Act<KIND>::eval(in[0], out[0], out[1]);
+    Act<KIND>::template eval<kWide>(in[0], out[0], out[1]);
   }
 };
 // Backward pass of the method: (gy, dydx) -> gx = gy * dydx.          Sec. II-C eq. 4
 struct BwdOp {
   static constexpr int kIn = 2, kOut = 1;
+  template <bool kWide>
   __device__ __forceinline__ static void apply(const float (&in)[kIn], float (&out)[kOut]) {
     out[0] = in[0] * in[1];
   }
@@ -122,15 +126,17 @@ struct BwdOp {
 template <int KIND>
 struct RecomputeFwdOp {
   static constexpr int kIn = 1, kOut = 1;
+  template <bool kWide>
   __device__ __forceinline__ static void apply(const float (&in)[kIn], float (&out)[kOut]) {
-    out[0] = act_value<KIND>(in[0]);
+    out[0] = act_value<KIND, kWide>(in[0]);
   }
 };
 template <int KIND>
 struct RecomputeBwdOp {  // (gy, x) -> gy * f'(x)
   static constexpr int kIn = 2, kOut = 1;
+  template <bool kWide>
   __device__ __forceinline__ static void apply(const float (&in)[kIn], float (&out)[kOut]) {
-    out[0] = in[0] * act_deriv<KIND>(in[1]);
+    out[0] = in[0] * act_deriv<KIND, kWide>(in[1]);
   }
 };
 
@@ -145,6 +151,7 @@ struct SaveAllBwdOp;
 template <>
 struct SaveAllFwdOp<kSwish> {  // v1 = sigmoid(x), v2 = x, v3 = v1 v2; saves v1
   static constexpr int kIn = 1, kOut = 2;
+  template <bool kWide>
   __device__ __forceinline__ static void apply(const float (&in)[kIn], float (&out)[kOut]) {
     const float v1 = sigmoid_f(in[0]);
     out[0] = v1 * in[0];
@@ -154,6 +161,7 @@ struct SaveAllFwdOp<kSwish> {  // v1 = sigmoid(x), v2 = x, v3 = v1 v2; saves v1
 template <>
 struct SaveAllBwdOp<kSwish> {  // (g, x, v1):  x' = g v2 [v1 (1 - v1)] + g v1      eqs. 1-2
   static constexpr int kIn = 3, kOut = 1;
+  template <bool kWide>
   __device__ __forceinline__ static void apply(const float (&in)[kIn], float (&out)[kOut]) {
     const float g = in[0], v2 = in[1], v1 = in[2];
     out[0] = fma_(g * v2, v1 * (1.0f - v1), g * v1);
@@ -163,6 +171,7 @@ struct SaveAllBwdOp<kSwish> {  // (g, x, v1):  x' = g v2 [v1 (1 - v1)] + g v1   
 template <>
 struct SaveAllFwdOp<kMish> {  // t = tanh(softplus x), y = x t; saves t
   static constexpr int kIn = 1, kOut = 2;
+  template <bool kWide>
   __device__ __forceinline__ static void apply(const float (&in)[kIn], float (&out)[kOut]) {
     const float x = in[0];
     const float e = ex2(kLog2e * __builtin_fminf(x, 41.5f));
@@ -175,6 +184,7 @@ struct SaveAllFwdOp<kMish> {  // t = tanh(softplus x), y = x t; saves t
 template <>
 struct SaveAllBwdOp<kMish> {  // (g, x, t)
   static constexpr int kIn = 3, kOut = 1;
+  template <bool kWide>
   __device__ __forceinline__ static void apply(const float (&in)[kIn], float (&out)[kOut]) {
     const float g = in[0], x = in[1], t = in[2];
     const float g_t = g * x;                       // product node, towards tanh
@@ -187,6 +197,7 @@ struct SaveAllBwdOp<kMish> {  // (g, x, t)
 template <>
 struct SaveAllFwdOp<kGeluErf> {  // h = 0.5 x, s = 1 + erf(x/sqrt 2), y = h s; saves h, s
   static constexpr int kIn = 1, kOut = 3;
+  template <bool kWide>
   __device__ __forceinline__ static void apply(const float (&in)[kIn], float (&out)[kOut]) {
     const float x = in[0];
     const float h = 0.5f * x;
@@ -199,6 +210,7 @@ struct SaveAllFwdOp<kGeluErf> {  // h = 0.5 x, s = 1 + erf(x/sqrt 2), y = h s; s
 template <>
 struct SaveAllBwdOp<kGeluErf> {  // (g, x, h, s)
   static constexpr int kIn = 4, kOut = 1;
+  template <bool kWide>
   __device__ __forceinline__ static void apply(const float (&in)[kIn], float (&out)[kOut]) {
     const float g = in[0], x = in[1], h = in[2], s = in[3];
     const float g_h = g * s, g_s = g * h;          // product node
@@ -211,6 +223,7 @@ struct SaveAllBwdOp<kGeluErf> {  // (g, x, h, s)
 template <>
 struct SaveAllFwdOp<kGeluTanh> {  // t = tanh u, h = 0.5 x, s = 1 + t, y = h s; saves t, h, s
   static constexpr int kIn = 1, kOut = 4;
+  template <bool kWide>
   __device__ __forceinline__ static void apply(const float (&in)[kIn], float (&out)[kOut]) {
     const float x = in[0];
     const float x2 = __builtin_fminf(x * x, 1.0e30f);
@@ -227,6 +240,7 @@ struct SaveAllFwdOp<kGeluTanh> {  // t = tanh u, h = 0.5 x, s = 1 + t, y = h s; 
 template <>
 struct SaveAllBwdOp<kGeluTanh> {  // (g, x, t, h, s)
   static constexpr int kIn = 5, kOut = 1;
+  template <bool kWide>
   __device__ __forceinline__ static void apply(const float (&in)[kIn], float (&out)[kOut]) {
     const float g = in[0], x = in[1], t = in[2], h = in[3], s = in[4];
     const float g_h = g * s, g_s = g * h;          // product node
@@ -259,6 +273,7 @@ __global__ __launch_bounds__((LaunchShape<Op::kIn, Op::kOut>::kThreads)) void ew
   using Vec = typename S::Vec;
   using Shape = LaunchShape<Op::kIn, Op::kOut>;
   constexpr int kVec = S::kVec;
+  constexpr bool kWide = sizeof(T) == 4;
   constexpr int kThreads = Shape::kThreads;
   constexpr int kUnroll = Shape::kUnroll;
   constexpr bool kNt = Shape::kNtLoad;
@@ -282,7 +297,7 @@ __global__ __launch_bounds__((LaunchShape<Op::kIn, Op::kOut>::kThreads)) void ew
         float fin[Op::kIn], fout[Op::kOut];
 #pragma unroll
         for (int i = 0; i < Op::kIn; ++i) fin[i] = S::up(vin[j][i][e]);
-        Op::apply(fin, fout);
+        Op::template apply<kWide>(fin, fout);
 #pragma unroll
         for (int o = 0; o < Op::kOut; ++o) vout[o][e] = S::down(fout[o]);
       }
@@ -303,7 +318,7 @@ __global__ __launch_bounds__((LaunchShape<Op::kIn, Op::kOut>::kThreads)) void ew
         float fin[Op::kIn], fout[Op::kOut];
 #pragma unroll
         for (int i = 0; i < Op::kIn; ++i) fin[i] = S::up(vin[i][e]);
-        Op::apply(fin, fout);
+        Op::template apply<kWide>(fin, fout);
 #pragma unroll
         for (int o = 0; o < Op::kOut; ++o) vout[o][e] = S::down(fout[o]);
       }
@@ -315,7 +330,7 @@ __global__ __launch_bounds__((LaunchShape<Op::kIn, Op::kOut>::kThreads)) void ew
       float fin[Op::kIn], fout[Op::kOut];
 #pragma unroll
       for (int i = 0; i < Op::kIn; ++i) fin[i] = S::up(reinterpret_cast<const T*>(p.in[i])[k]);
-      Op::apply(fin, fout);
+      Op::template apply<kWide>(fin, fout);
 #pragma unroll
       for (int o = 0; o < Op::kOut; ++o) reinterpret_cast<T*>(p.out[o])[k] = S::down(fout[o]);
     }
@@ -327,12 +342,13 @@ __global__ __launch_bounds__((LaunchShape<Op::kIn, Op::kOut>::kThreads)) void ew
 template <class Op, typename T>
 __global__ __launch_bounds__(kScalarThreads) void ew_scalar_kernel(Ptrs<Op::kIn, Op::kOut> p, size_t n) {
   using S = Storage<T>;
+  constexpr bool kWide = sizeof(T) == 4;
   const size_t stride = (size_t)gridDim.x * kScalarThreads;
   for (size_t k = (size_t)blockIdx.x * kScalarThreads + threadIdx.x; k < n; k += stride) {
     float fin[Op::kIn], fout[Op::kOut];
 #pragma unroll
     for (int i = 0; i < Op::kIn; ++i) fin[i] = S::up(reinterpret_cast<const T*>(p.in[i])[k]);
-    Op::apply(fin, fout);
+    Op::template apply<kWide>(fin, fout);
 #pragma unroll
     for (int o = 0; o < Op::kOut; ++o) reinterpret_cast<T*>(p.out[o])[k] = S::down(fout[o]);
   }
