@@ -110,14 +110,16 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     value = bytes_per_step / (ms_per_step * 1e-3) / 1e9
 
-    # ---- per-kernel launch duration: events on the launch stream around back-to-back launches
+    # ---- per-kernel launch duration: events on the launch stream around back-to-back launches.
+    # Warm-up launches are queued right in front of the timed region (no idle gap, so clocks and
+    # caches are in steady state when the first event fires).
     per_kernel = {}
     for name, (fn, words) in kernels.items():
-        for i in range(max(3, args.warmup // 4)):
-            fn(sets[i % nsets])
         e0 = torch.cuda.Event(enable_timing=True)
         e1 = torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
+        for i in range(max(5, args.warmup)):
+            fn(sets[i % nsets])
         e0.record(stream)
         for i in range(args.steps):
             fn(sets[i % nsets])
@@ -128,6 +130,21 @@ def main():
         per_kernel[name] = {"us": round(us, 2), "bytes_per_elem": words * es, "GB/s": round(gbps, 1),
                             "frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4),
                             "Gelem/s": round(n / (us * 1e-6) / 1e9, 1)}
+
+    # ---- context: the runtime's own device-to-device copy of the same tensor (n read + n written)
+    for i in range(3):
+        sets[i % nsets]["y"].copy_(sets[i % nsets]["x"])
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record(stream)
+    for i in range(args.steps):
+        sets[i % nsets]["y"].copy_(sets[i % nsets]["x"])
+    e1.record(stream)
+    torch.cuda.synchronize()
+    copy_us = e0.elapsed_time(e1) * 1e3 / args.steps
+    reference_copy = {"what": "runtime device-to-device copy of x (hipMemcpyAsync via torch copy_)",
+                      "us": round(copy_us, 2), "GB/s": round(2 * n * es / (copy_us * 1e-6) / 1e9, 1)}
 
     for i in range(args.calib_copy):      # plain copy of known size, for counter calibration only
         sets[i % nsets]["y"].copy_(sets[i % nsets]["x"])
@@ -177,8 +194,15 @@ def main():
         _, saved64 = oracle.saveall_fwd(kind, x64)
         oracle.saveall_bwd(kind, gy64, saved64)
         c1 = time.perf_counter()
+        # once single-threaded, on a sixteenth of the sample
+        n1 = max(1, ns // 16)
+        s0 = time.perf_counter()
+        y1, d1 = oracle.fwd(kind, x64[:n1], threads=1)
+        oracle.bwd(gy64[:n1], d1, threads=1)
+        s1 = time.perf_counter()
         cpu_baseline = {
             "value": round(words_per_step * ns * es / (c1 - c0) / 1e9, 3), "unit": "GB/s",
+            "single_thread_fwd_bwd_Gelem/s": round(n1 / (s1 - s0) / 1e9, 4),
             "cores": threads, "kind": "oracle",
             "sample": f"first {ns} of {n} elements, one step (all six passes) in fp64 with OpenMP, "
                       f"{c1 - c0:.2f} s wall; bytes counted as for the {dtype} GPU step",
@@ -197,6 +221,7 @@ def main():
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
         "Gelem/s": round(6 * n / (ms_per_step * 1e-3) / 1e9, 1),
         "roofline": roofline, "cpu_baseline": cpu_baseline, "kernels": per_kernel, "summary": summary,
+        "reference_copy": reference_copy,
     }
     print(json.dumps(out))
 

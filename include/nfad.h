@@ -34,7 +34,8 @@
  *             launch (pointers may then be NULL).  A failed launch gives NFAD_ELAUNCH.
  *             Nothing throws or aborts across this boundary.
  * Finite x  : for every finite input the results are finite: y -> x, dydx -> 1 as
- *             x -> +inf and y -> -0, dydx -> -0 as x -> -inf.
+ *             x -> +inf and y -> -0, dydx -> -0 as x -> -inf.  A NaN input gives NaN in
+ *             every output of that element; +-inf inputs give unspecified values.
  */
 #ifndef NFAD_H_
 #define NFAD_H_

@@ -174,7 +174,7 @@ struct SaveAllFwdOp<kMish> {  // t = tanh(softplus x), y = x t; saves t
   template <bool kWide>
   __device__ __forceinline__ static void apply(const float (&in)[kIn], float (&out)[kOut]) {
     const float x = in[0];
-    const float e = ex2(kLog2e * __builtin_fminf(x, 41.5f));
+    const float e = ex2(kLog2e * mish_cap(x));
     const float n = fma_(e, e, e + e);
     const float t = n * rcp(n + 2.0f);
     out[0] = x * t;

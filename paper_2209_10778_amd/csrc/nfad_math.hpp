@@ -138,13 +138,15 @@ struct Act<kGeluErf> {
 // 1 - t^2 = 4 (e + 1)^2 / (n + 2)^2, softplus' = e / (e + 1), hence
 //     dydx = t + x * 4 e (e + 1) / (n + 2)^2.
 // x is capped at 41.5 (< 60 ln 2) inside the exponential (t and dydx are already 1 to fp32
-// precision far below that) so that n cannot overflow.  Wide tier: for x > 0,
+// precision far below that) so that n cannot overflow; the cap is a compare-and-select, not
+// a min, so that a NaN input stays NaN in both results.  Wide tier: for x > 0,
 // y = x - 2x/(n+2) keeps the last bits that x * t would lose.
+__device__ __forceinline__ float mish_cap(float x) { return x > 41.5f ? 41.5f : x; }
 template <>
 struct Act<kMish> {
   template <bool kWide>
   __device__ __forceinline__ static void eval(float x, float& y, float& d) {
-    const float xc = __builtin_fminf(x, 41.5f);
+    const float xc = mish_cap(x);
     const float e = ex2(kLog2e * xc);
     const float n = fma_(e, e, e + e);
     const float R = rcp(n + 2.0f);

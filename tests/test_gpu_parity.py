@@ -274,6 +274,33 @@ def test_exact_aliasing_is_allowed():
     assert ei.value.status == 5
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_nan_inputs_stay_nan(dtype):
+    """A NaN activation must not be laundered into a finite value or derivative."""
+    td = DTYPES[dtype]
+    n = 4099
+    x = stress_x(n, 9500, dtype)
+    idx = torch.tensor([0, 1, 7, 8, 63, 64, 1000, 2048, 4096, 4098])
+    x[idx] = float("nan")
+    xd = dev(x)
+    gy = dev(inputs.to_storage(inputs.gaussian(n, 1.0, 9501), dtype))
+    nanmask = torch.isnan(xd.float())
+    for kind in nfad.KINDS:
+        y, d, gx = torch.empty_like(xd), torch.empty_like(xd), torch.empty_like(xd)
+        nfad.nfad_fwd(kind, xd, y, d)
+        nfad.nfad_bwd(gy, d, gx)
+        for name, t in (("y", y), ("dydx", d), ("gx", gx)):
+            assert bool(torch.equal(torch.isnan(t.float()), nanmask)), f"{name} kind={kind} {dtype}"
+        nfad.nfad_recompute_fwd(kind, xd, y)
+        nfad.nfad_recompute_bwd(kind, gy, xd, gx)
+        assert bool(torch.equal(torch.isnan(y.float()), nanmask)) and bool(torch.equal(torch.isnan(gx.float()), nanmask))
+        k = nfad.nfad_saveall_num_saved(kind)
+        saved = [xd] + [torch.empty_like(xd) for _ in range(k - 1)]
+        nfad.nfad_saveall_fwd(kind, xd, y, saved)
+        nfad.nfad_saveall_bwd(kind, gy, saved, gx)
+        assert bool(torch.equal(torch.isnan(y.float()), nanmask)) and bool(torch.equal(torch.isnan(gx.float()), nanmask))
+
+
 def test_non_default_stream():
     kind, dtype, td = nfad.MISH, "bf16", torch.bfloat16
     x = stress_x(N_RAGGED, 9000, dtype)
