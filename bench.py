@@ -37,6 +37,8 @@ def parse_args():
     ap.add_argument("--calib-copy", type=int, default=0,
                     help="also launch this many plain device copies of x (n elements read, n written): the "
                          "known-size kernel that rocprofv3 FETCH_SIZE/WRITE_SIZE readings are scaled by")
+    ap.add_argument("--chains", action="store_true",
+                    help="also time the fused forward kernel of every composed chain on the same tensor")
     ap.add_argument("--cpu-sample", type=int, default=1 << 25, help="max elements the oracle is timed on")
     return ap.parse_args()
 
@@ -150,6 +152,26 @@ def main():
         sets[i % nsets]["y"].copy_(sets[i % nsets]["x"])
     torch.cuda.synchronize()
 
+    chains = None
+    if args.chains:   # composed chains: same contract and traffic as nfad_fwd (3 words per element)
+        chains = {}
+        for cid in range(nfad.nfad_chain_count()):
+            fn = lambda s, cid=cid: nfad.nfad_chain_fwd(cid, s["x"], s["y"], s["dydx"], stream)
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            for i in range(max(5, args.warmup)):
+                fn(sets[i % nsets])
+            e0.record(stream)
+            for i in range(args.steps):
+                fn(sets[i % nsets])
+            e1.record(stream)
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / args.steps
+            gbps = 3 * n * es / (us * 1e-6) / 1e9
+            chains[nfad.nfad_chain_name(cid)] = {"us": round(us, 2), "GB/s": round(gbps, 1),
+                                                 "frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4)}
+
     fwd = per_kernel["nfad_fwd"]
     roofline = {"kernel": "nfad_fwd", "bound": "hbm", "achieved": fwd["GB/s"], "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(fwd["GB/s"] / HBM_PEAK_GBPS, 4), "traffic": None,
@@ -221,7 +243,7 @@ def main():
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
         "Gelem/s": round(6 * n / (ms_per_step * 1e-3) / 1e9, 1),
         "roofline": roofline, "cpu_baseline": cpu_baseline, "kernels": per_kernel, "summary": summary,
-        "reference_copy": reference_copy,
+        "reference_copy": reference_copy, "chains": chains,
     }
     print(json.dumps(out))
 

@@ -100,6 +100,24 @@ int nfad_saveall_fwd(int kind, const void* x, void* y, void* const* saved, size_
 int nfad_saveall_bwd(int kind, const void* gy, const void* const* saved, void* gx, size_t n,
                      int dtype, void* stream);
 
+/* Composed chains (Sec. III-A: any composition of "fad" primitive operations that maps one
+ * source element to one result; primitives: + - * / neg exp log tanh sigmoid softplus erf,
+ * constants, and the source x).  The library carries a table of chains built from those
+ * primitives with a compile-time dual-number composer; each is fused into ONE forward
+ * kernel with the contract of nfad_fwd: y[i] = f(x[i]), dydx[i] = f'(x[i]), f' obtained by
+ * pushing the dual number (x, 1) through the primitives (Sec. II-C eq. 3, Sec. II-D).
+ * The backward pass of a chain is nfad_bwd.
+ *   nfad_chain_count    number of chains in the table (ids are 0 .. count-1)
+ *   nfad_chain_name     short name, or NULL for a bad id
+ *   nfad_chain_program  the chain in postfix notation over the primitive names, e.g.
+ *                       "x x softplus tanh *" for x*tanh(softplus(x)); NULL for a bad id
+ *   nfad_chain_fwd      as nfad_fwd; a bad id gives NFAD_EINVAL_KIND */
+int nfad_chain_count(void);
+const char* nfad_chain_name(int chain_id);
+const char* nfad_chain_program(int chain_id);
+int nfad_chain_fwd(int chain_id, const void* x, void* y, void* dydx, size_t n, int dtype,
+                   void* stream);
+
 /* Static, NUL-terminated description of a status code (never NULL). */
 const char* nfad_status_string(int status);
 

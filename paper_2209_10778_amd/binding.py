@@ -47,10 +47,16 @@ def lib() -> ctypes.CDLL:
         L.nfad_saveall_num_saved.argtypes = [ci]
         L.nfad_saveall_fwd.argtypes = [ci, vp, vp, vpp, sz, ci, vp]
         L.nfad_saveall_bwd.argtypes = [ci, vp, vpp, vp, sz, ci, vp]
+        L.nfad_chain_fwd.argtypes = [ci, vp, vp, vp, sz, ci, vp]
+        L.nfad_chain_name.argtypes = [ci]
+        L.nfad_chain_name.restype = ctypes.c_char_p
+        L.nfad_chain_program.argtypes = [ci]
+        L.nfad_chain_program.restype = ctypes.c_char_p
         L.nfad_status_string.argtypes = [ci]
         L.nfad_status_string.restype = ctypes.c_char_p
         for name in ("nfad_fwd", "nfad_bwd", "nfad_recompute_fwd", "nfad_recompute_bwd",
-                     "nfad_saveall_num_saved", "nfad_saveall_fwd", "nfad_saveall_bwd", "nfad_version"):
+                     "nfad_saveall_num_saved", "nfad_saveall_fwd", "nfad_saveall_bwd", "nfad_version",
+                     "nfad_chain_count", "nfad_chain_fwd"):
             getattr(L, name).restype = ci
         _lib = L
     return _lib
@@ -140,6 +146,26 @@ def nfad_saveall_bwd(kind, gy, saved, gx, stream=None) -> None:
     n, dt = _marshal(gy, gx, *saved)
     _check(lib().nfad_saveall_bwd(int(kind), gy.data_ptr(), _ptr_array(saved), gx.data_ptr(), n, dt,
                                   _stream(stream)), "nfad_saveall_bwd")
+
+
+def nfad_chain_count() -> int:
+    return int(lib().nfad_chain_count())
+
+
+def nfad_chain_name(chain_id: int):
+    r = lib().nfad_chain_name(int(chain_id))
+    return None if r is None else r.decode()
+
+
+def nfad_chain_program(chain_id: int):
+    r = lib().nfad_chain_program(int(chain_id))
+    return None if r is None else r.decode()
+
+
+def nfad_chain_fwd(chain_id, x, y, dydx, stream=None) -> None:
+    n, dt = _marshal(x, y, dydx)
+    _check(lib().nfad_chain_fwd(int(chain_id), x.data_ptr(), y.data_ptr(), dydx.data_ptr(), n, dt,
+                                _stream(stream)), "nfad_chain_fwd")
 
 
 def nfad_status_string(status: int) -> str:

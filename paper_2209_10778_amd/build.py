@@ -6,7 +6,7 @@ import subprocess
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRC = os.path.join(HERE, "csrc", "nfad_kernels.hip")
+SRCS = [os.path.join(HERE, "csrc", f) for f in ("nfad_kernels.hip", "nfad_chain.hip")]
 LIB = os.path.join(HERE, "libnfad.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -19,7 +19,7 @@ FLAGS = [
 
 
 def build(extra_flags=(), out=LIB, verbose=True) -> str:
-    cmd = [HIPCC, *FLAGS, *extra_flags, "-o", out, SRC]
+    cmd = [HIPCC, *FLAGS, *extra_flags, "-o", out, *SRCS]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)

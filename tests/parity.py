@@ -28,7 +28,8 @@ def tolerance(ref: torch.Tensor, dtype: torch.dtype) -> torch.Tensor:
     return torch.clamp(ulp_of(ref, dtype), min=ABS_FLOOR)
 
 
-def compare(got: torch.Tensor, ref64, dtype: torch.dtype, what: str = "", flat_abs: float | None = None):
+def compare(got: torch.Tensor, ref64, dtype: torch.dtype, what: str = "", flat_abs: float | None = None,
+            extra_tol=None):
     """Element-by-element check of a storage tensor against float64 reference values.
     Returns a dict of statistics; raises AssertionError naming the worst element."""
     dev = got.device
@@ -41,6 +42,8 @@ def compare(got: torch.Tensor, ref64, dtype: torch.dtype, what: str = "", flat_a
     assert bool(finite.all()), f"{what}: {int((~finite).sum())} non-finite outputs"
     err = (g - ref).abs()
     tol = tolerance(ref, dtype) if flat_abs is None else torch.full_like(ref, flat_abs)
+    if extra_tol is not None:   # per-element allowance on top (float64 array-like)
+        tol = tol + torch.as_tensor(np.asarray(extra_tol), dtype=torch.float64).reshape(-1).to(dev)
     bad = err > tol
     ulps = err / ulp_of(ref, dtype)
     stats = {

@@ -21,7 +21,8 @@ def declared_functions():
 def test_header_declares_the_expected_entry_points():
     assert declared_functions() == sorted([
         "nfad_fwd", "nfad_bwd", "nfad_recompute_fwd", "nfad_recompute_bwd", "nfad_saveall_num_saved",
-        "nfad_saveall_fwd", "nfad_saveall_bwd", "nfad_status_string", "nfad_version"])
+        "nfad_saveall_fwd", "nfad_saveall_bwd", "nfad_status_string", "nfad_version",
+        "nfad_chain_count", "nfad_chain_name", "nfad_chain_program", "nfad_chain_fwd"])
 
 
 def test_library_exports_every_declared_symbol():

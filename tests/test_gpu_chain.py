@@ -1,0 +1,83 @@
+"""GPU parity of the composed chains: every chain the library carries, through the C ABI,
+against the fp64 postfix dual-number interpreter on the same seeded storage-rounded inputs."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import chain
+import oracle
+import paper_2209_10778_amd as nfad
+from paper_2209_10778_amd import inputs
+from parity import compare
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+DTYPES = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+N = 3 * 8192 + 5 * 256 + 77 + 5
+
+
+def chains():
+    return [(i, nfad.nfad_chain_name(i)) for i in range(nfad.nfad_chain_count())]
+
+
+def chain_inputs(name, dtype, seed):
+    """N(0, 2.5) clipped to the range where the chain as spelled is finite in fp32 and in the
+    storage type (exp(x) leaves fp16 above 11; the quotient form of Swish needs e^-x finite)."""
+    a = inputs.gaussian(N, 2.5, seed)
+    lim = {"exp": 10.0, "swish_table1": 60.0}.get(name, 100.0)
+    special = np.array([0.0, -0.0, 1e-4, -1e-4, 0.02, -0.02, 0.1, -0.1, 1.0, -1.0, 5.0, -5.0, 9.0, -9.0,
+                        20.0, -20.0, 50.0, -50.0, 80.0, -80.0], np.float32)
+    a[:special.size] = special
+    return inputs.to_storage(np.clip(a, -lim, lim), dtype)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("cid,name", chains())
+def test_chain_fwd_matches_interpreter(cid, name, dtype):
+    td = DTYPES[dtype]
+    x = chain_inputs(name, dtype, 7000 + cid)
+    x64 = inputs.storage_to_f64(x)
+    y_ref, d_ref = chain.eval_chain(nfad.nfad_chain_program(cid), x64)
+    xd = x.to(DEV)
+    y = torch.full_like(xd, float("nan"))
+    d = torch.full_like(xd, float("nan"))
+    nfad.nfad_chain_fwd(cid, xd, y, d)
+    # fp32 arithmetic through a composition: a few fp32 ulps per primitive, and the exponent
+    # argument's rounding scales with |x|; allow 2e-6 * max(1,|x|) relative on top of the usual bar
+    rel = 2e-6 * np.maximum(1.0, np.abs(x64))
+    sy = compare(y, y_ref, td, f"chain {name} y {dtype}", extra_tol=rel * np.maximum(1.0, np.abs(y_ref)))
+    sd = compare(d, d_ref, td, f"chain {name} dydx {dtype}", extra_tol=rel * np.maximum(1.0, np.abs(d_ref)))
+    print(f"\n[chain {name} {dtype}] y max_abs {sy['max_abs']:.3e} max_ulp {sy['max_ulp']:.2f}; "
+          f"dydx max_abs {sd['max_abs']:.3e} max_ulp {sd['max_ulp']:.2f}")
+
+
+def test_chain_then_bwd_gives_the_chain_gradient():
+    """Sec. II-E: dL/dx = (d chain/dx) * g, with the stored tangent of the fused forward."""
+    td, dtype = torch.float32, "f32"
+    cid = [i for i, n in chains() if n == "tanhshrink"][0]
+    x = chain_inputs("tanhshrink", dtype, 7100)
+    gy = inputs.to_storage(inputs.gaussian(N, 1.0, 7101), dtype)
+    x64, gy64 = inputs.storage_to_f64(x), inputs.storage_to_f64(gy)
+    _, d_ref = chain.eval_chain(nfad.nfad_chain_program(cid), x64)
+    xd, gyd = x.to(DEV), gy.to(DEV)
+    y, d, gx = torch.empty_like(xd), torch.empty_like(xd), torch.empty_like(xd)
+    nfad.nfad_chain_fwd(cid, xd, y, d)
+    nfad.nfad_bwd(gyd, d, gx)
+    compare(gx, oracle.bwd(gy64, d_ref), td, "chain gradient", extra_tol=4e-6 * np.abs(gy64) * np.maximum(1.0, np.abs(x64)))
+
+
+def test_chain_errors_and_edges():
+    L = nfad.lib()
+    A = 1 << 20
+    assert L.nfad_chain_fwd(-1, A, A + 64, A + 128, 4, 0, None) == 1
+    assert L.nfad_chain_fwd(nfad.nfad_chain_count(), A, A + 64, A + 128, 4, 0, None) == 1
+    assert L.nfad_chain_fwd(0, None, None, None, 0, 0, None) == 0
+    assert L.nfad_chain_fwd(0, None, A, A + 64, 4, 0, None) == 3
+    for n in (1, 3, 7, 8, 9, 255, 257):
+        x = chain_inputs("sigmoid", "bf16", 7200 + n)[:n].contiguous()
+        y_ref, d_ref = chain.eval_chain("x sigmoid", inputs.storage_to_f64(x))
+        xd = x.to(DEV)
+        y, d = torch.empty_like(xd), torch.empty_like(xd)
+        nfad.nfad_chain_fwd(0, xd, y, d)
+        compare(y, y_ref, torch.bfloat16, f"n={n}")
+        compare(d, d_ref, torch.bfloat16, f"n={n}")
