@@ -64,7 +64,9 @@ typedef enum {
   NFAD_ENULL = 3,   /* a required pointer is NULL while n > 0            */
   NFAD_EALIGN = 4,  /* a pointer is not aligned to the element size      */
   NFAD_EALIAS = 5,  /* two outputs of one call coincide                  */
-  NFAD_ELAUNCH = 6  /* the HIP runtime refused the launch                */
+  NFAD_ELAUNCH = 6, /* the HIP runtime refused the launch                */
+  NFAD_EPROGRAM = 7, /* a chain program is malformed                      */
+  NFAD_ECOMPILE = 8  /* run-time compilation or loading of a chain failed */
 } nfad_status_t;
 
 #define NFAD_MAX_SAVED 4
@@ -117,6 +119,26 @@ const char* nfad_chain_name(int chain_id);
 const char* nfad_chain_program(int chain_id);
 int nfad_chain_fwd(int chain_id, const void* x, void* y, void* dydx, size_t n, int dtype,
                    void* stream);
+
+/* Run-time composed chains: the counterpart of the paper's automatic graph rewrite
+ * (Sec. III-B, Sec. IV), which finds a chain of fad operations and replaces its forward and
+ * backward passes.  `program` is ANY chain in the postfix notation above (tokens separated
+ * by blanks: x, decimal constants, + - * / neg exp log tanh sigmoid softplus erf; at most
+ * 256 tokens; must use x and leave exactly one value).  The library compiles one fused
+ * forward kernel for it on the current device (hiprtc; about a second) and returns a chain
+ * id >= NFAD_CHAIN_JIT_BASE in *chain_id, valid for nfad_chain_fwd / _name / _program on
+ * that device until released.  This is the one stateful part of the library: the table of
+ * compiled chains is process-wide and protected by a mutex.
+ *   nfad_chain_compile  NFAD_EPROGRAM for a malformed program (checked on the host before
+ *                       any compiler or HIP call), NFAD_ECOMPILE if compiling or loading fails
+ *   nfad_chain_release  unloads the kernel; the caller must first wait for launches of that
+ *                       chain to finish.  NFAD_EINVAL_KIND for an id that is not live
+ *   nfad_chain_log      the calling thread's message from its last nfad_chain_compile
+ *                       (parse error or compiler log; empty string if none) */
+#define NFAD_CHAIN_JIT_BASE 1000
+int nfad_chain_compile(const char* program, int* chain_id);
+int nfad_chain_release(int chain_id);
+const char* nfad_chain_log(void);
 
 /* Static, NUL-terminated description of a status code (never NULL). */
 const char* nfad_status_string(int status);

@@ -52,11 +52,14 @@ def lib() -> ctypes.CDLL:
         L.nfad_chain_name.restype = ctypes.c_char_p
         L.nfad_chain_program.argtypes = [ci]
         L.nfad_chain_program.restype = ctypes.c_char_p
+        L.nfad_chain_compile.argtypes = [ctypes.c_char_p, ctypes.POINTER(ci)]
+        L.nfad_chain_release.argtypes = [ci]
+        L.nfad_chain_log.restype = ctypes.c_char_p
         L.nfad_status_string.argtypes = [ci]
         L.nfad_status_string.restype = ctypes.c_char_p
         for name in ("nfad_fwd", "nfad_bwd", "nfad_recompute_fwd", "nfad_recompute_bwd",
                      "nfad_saveall_num_saved", "nfad_saveall_fwd", "nfad_saveall_bwd", "nfad_version",
-                     "nfad_chain_count", "nfad_chain_fwd"):
+                     "nfad_chain_count", "nfad_chain_fwd", "nfad_chain_compile", "nfad_chain_release"):
             getattr(L, name).restype = ci
         _lib = L
     return _lib
@@ -166,6 +169,23 @@ def nfad_chain_fwd(chain_id, x, y, dydx, stream=None) -> None:
     n, dt = _marshal(x, y, dydx)
     _check(lib().nfad_chain_fwd(int(chain_id), x.data_ptr(), y.data_ptr(), dydx.data_ptr(), n, dt,
                                 _stream(stream)), "nfad_chain_fwd")
+
+
+def nfad_chain_compile(program: str) -> int:
+    """Compile a postfix chain program into a fused forward kernel; returns its chain id."""
+    cid = ctypes.c_int(-1)
+    status = lib().nfad_chain_compile(program.encode(), ctypes.byref(cid))
+    if status != 0:
+        raise NfadError(status, f"nfad_chain_compile({program!r}): {nfad_chain_log()}")
+    return int(cid.value)
+
+
+def nfad_chain_release(chain_id: int) -> None:
+    _check(lib().nfad_chain_release(int(chain_id)), "nfad_chain_release")
+
+
+def nfad_chain_log() -> str:
+    return (lib().nfad_chain_log() or b"").decode(errors="replace")
 
 
 def nfad_status_string(status: int) -> str:

@@ -6,18 +6,6 @@
 
 namespace nfad {
 
-// Forward pass of a composed chain: (x) -> (value, tangent) of Chain at (x, 1).   Sec. II-C eq. 3
-template <class Chain>
-struct ChainFwdOp {
-  static constexpr int kIn = 1, kOut = 2;
-  template <bool kWide>
-  __device__ __forceinline__ static void apply(const float (&in)[kIn], float (&out)[kOut]) {
-    const chain::Dual r = Chain::eval(chain::seed(in[0]));
-    out[0] = r.v;
-    out[1] = r.d;
-  }
-};
-
 namespace chain {
 NFAD_CHAIN_CONSTANT(kOne, 1.0f);
 NFAD_CHAIN_CONSTANT(kHalf, 0.5f);
@@ -65,6 +53,16 @@ static constexpr int kNumChains = (int)(sizeof(kChains) / sizeof(kChains[0]));
 
 }  // namespace nfad
 
+namespace nfad {
+namespace jit {
+struct Compiled;
+static const Compiled* find(int chain_id);
+static int forward(const Compiled* c, const void* x, void* y, void* dydx, size_t n, int dtype, void* stream);
+static const char* name_of(const Compiled* c);
+static const char* program_of(const Compiled* c);
+}  // namespace jit
+}  // namespace nfad
+
 using namespace nfad;
 
 extern "C" {
@@ -72,14 +70,26 @@ extern "C" {
 int nfad_chain_count(void) { return kNumChains; }
 
 const char* nfad_chain_name(int chain_id) {
+  if (chain_id >= NFAD_CHAIN_JIT_BASE) {
+    const jit::Compiled* c = jit::find(chain_id);
+    return c ? jit::name_of(c) : nullptr;
+  }
   return (chain_id >= 0 && chain_id < kNumChains) ? kChains[chain_id].name : nullptr;
 }
 
 const char* nfad_chain_program(int chain_id) {
+  if (chain_id >= NFAD_CHAIN_JIT_BASE) {
+    const jit::Compiled* c = jit::find(chain_id);
+    return c ? jit::program_of(c) : nullptr;
+  }
   return (chain_id >= 0 && chain_id < kNumChains) ? kChains[chain_id].program : nullptr;
 }
 
 int nfad_chain_fwd(int chain_id, const void* x, void* y, void* dydx, size_t n, int dtype, void* stream) {
+  if (chain_id >= NFAD_CHAIN_JIT_BASE) {
+    const jit::Compiled* c = jit::find(chain_id);
+    return c ? jit::forward(c, x, y, dydx, n, dtype, stream) : NFAD_EINVAL_KIND;
+  }
   if (chain_id < 0 || chain_id >= kNumChains) return NFAD_EINVAL_KIND;
   const void* const in[1] = {x};
   void* const out[2] = {y, dydx};
@@ -98,5 +108,213 @@ int nfad_chain_fwd(int chain_id, const void* x, void* y, void* dydx, size_t n, i
   }
   return NFAD_EINVAL_KIND;
 }
+
+}  // extern "C"
+
+// ==================================================================== run-time composed chains
+// A caller can hand the library ANY chain over the primitives, as a postfix program; the
+// library translates it into the same expression-template type the built-in chains use,
+// compiles that one instantiation of the streaming kernel with the run-time compiler
+// (hiprtc, for the architecture of the current device) and keeps the loaded kernel under a
+// new chain id.  The program text is parsed against a closed grammar (the primitive names,
+// `x`, decimal constants): nothing from the caller's string reaches the compiler verbatim.
+#include <hip/hiprtc.h>
+
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "nfad_embedded.inc"
+
+namespace nfad {
+namespace jit {
+
+static constexpr int kMaxTokens = 256;
+static constexpr int kMaxChains = 4096;
+
+struct Compiled {
+  std::string program, name;
+  hipModule_t module = nullptr;
+  hipFunction_t vec[3] = {nullptr, nullptr, nullptr};     // indexed by nfad_dtype_t
+  hipFunction_t scalar[3] = {nullptr, nullptr, nullptr};
+  bool live = false;
+};
+static std::mutex g_mu;
+static std::vector<Compiled*> g_chains;          // index = id - NFAD_CHAIN_JIT_BASE; never shrinks
+static thread_local std::string g_log;
+
+// postfix program -> C++ type expression over nfad::chain templates (+ constant definitions)
+static bool translate(const char* program, std::string& consts, std::string& type, std::string& err) {
+  static const struct { const char* tok; const char* tmpl; int arity; } kOps[] = {
+      {"+", "Add", 2}, {"-", "Sub", 2}, {"*", "Mul", 2}, {"/", "Div", 2}, {"neg", "Neg", 1},
+      {"exp", "Exp", 1}, {"log", "Log", 1}, {"tanh", "Tanh", 1}, {"sigmoid", "Sigmoid", 1},
+      {"softplus", "Softplus", 1}, {"erf", "Erf", 1}};
+  std::vector<std::string> stack;
+  int ntok = 0, nconst = 0;
+  bool uses_x = false;
+  const char* p = program;
+  while (*p) {
+    while (*p == ' ' || *p == '\t' || *p == '\n') ++p;
+    if (!*p) break;
+    const char* q = p;
+    while (*q && *q != ' ' && *q != '\t' && *q != '\n') ++q;
+    const std::string tok(p, q);
+    p = q;
+    if (++ntok > kMaxTokens) { err = "program too long"; return false; }
+    if (tok == "x") { stack.push_back("X"); uses_x = true; continue; }
+    bool matched = false;
+    for (const auto& op : kOps) {
+      if (tok != op.tok) continue;
+      if ((int)stack.size() < op.arity) { err = "operator '" + tok + "' lacks operands"; return false; }
+      if (op.arity == 1) {
+        stack.back() = std::string(op.tmpl) + "<" + stack.back() + ">";
+      } else {
+        const std::string b = stack.back(); stack.pop_back();
+        stack.back() = std::string(op.tmpl) + "<" + stack.back() + ", " + b + ">";
+      }
+      matched = true;
+      break;
+    }
+    if (matched) continue;
+    char* end = nullptr;
+    const float c = strtof(tok.c_str(), &end);
+    if (end == tok.c_str() || *end != '\0' || !isfinite(c)) { err = "unknown token '" + tok + "'"; return false; }
+    char buf[96];
+    snprintf(buf, sizeof buf, "NFAD_CHAIN_CONSTANT(K%d, %af);\n", nconst, (double)c);  // exact hex-float literal
+    consts += buf;
+    stack.push_back("Const<K" + std::to_string(nconst) + ">");
+    ++nconst;
+  }
+  if (stack.size() != 1) { err = "program leaves " + std::to_string(stack.size()) + " values"; return false; }
+  if (!uses_x) { err = "program does not use x"; return false; }
+  type = stack[0];
+  return true;
+}
+
+static const char* kTypeNames[3] = {"float", "_Float16", "__bf16"};   // indexed by nfad_dtype_t
+
+static int compile(const char* program, int* chain_id) {
+  std::string consts, type, err;
+  g_log.clear();
+  if (!translate(program, consts, type, err)) { g_log = err; return NFAD_EPROGRAM; }
+
+  const std::string src = "#include \"nfad_stream_device.hpp\"\n#include \"nfad_chain.hpp\"\n"
+                          "namespace nfad { namespace chain {\n" + consts + "using UserChain = " + type +
+                          ";\n} }\n";
+  hiprtcProgram prog = nullptr;
+  if (hiprtcCreateProgram(&prog, src.c_str(), "nfad_user_chain.hip", kNumEmbedded, const_cast<const char**>(kEmbeddedSources),
+                          const_cast<const char**>(kEmbeddedNames)) != HIPRTC_SUCCESS) {
+    g_log = "hiprtcCreateProgram failed";
+    return NFAD_ECOMPILE;
+  }
+  std::string names[6];
+  for (int t = 0; t < 3; ++t) {
+    names[t] = std::string("nfad::ew_vec_kernel<nfad::ChainFwdOp<nfad::chain::UserChain>, ") + kTypeNames[t] + ">";
+    names[3 + t] = std::string("nfad::ew_scalar_kernel<nfad::ChainFwdOp<nfad::chain::UserChain>, ") + kTypeNames[t] + ">";
+  }
+  for (auto& nm : names) hiprtcAddNameExpression(prog, nm.c_str());
+
+  int dev = 0;
+  hipDeviceProp_t prop;
+  std::string arch = "gfx950";
+  if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.gcnArchName[0])
+    arch = prop.gcnArchName;
+  const std::string arch_opt = "--offload-arch=" + arch;
+  const char* opts[] = {arch_opt.c_str(), "-O3", "-std=c++17",
+                        "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"};
+  const hiprtcResult rc = hiprtcCompileProgram(prog, (int)(sizeof(opts) / sizeof(opts[0])), opts);
+  size_t log_size = 0;
+  if (hiprtcGetProgramLogSize(prog, &log_size) == HIPRTC_SUCCESS && log_size > 1) {
+    g_log.resize(log_size);
+    hiprtcGetProgramLog(prog, &g_log[0]);
+  }
+  if (rc != HIPRTC_SUCCESS) { hiprtcDestroyProgram(&prog); return NFAD_ECOMPILE; }
+
+  size_t code_size = 0;
+  std::vector<char> code;
+  if (hiprtcGetCodeSize(prog, &code_size) != HIPRTC_SUCCESS) { hiprtcDestroyProgram(&prog); return NFAD_ECOMPILE; }
+  code.resize(code_size);
+  hiprtcGetCode(prog, code.data());
+
+  Compiled* c = new Compiled;
+  c->program = program;
+  bool ok = hipModuleLoadData(&c->module, code.data()) == hipSuccess;
+  for (int t = 0; ok && t < 6; ++t) {
+    const char* lowered = nullptr;
+    ok = hiprtcGetLoweredName(prog, names[t].c_str(), &lowered) == HIPRTC_SUCCESS && lowered &&
+         hipModuleGetFunction(t < 3 ? &c->vec[t] : &c->scalar[t - 3], c->module, lowered) == hipSuccess;
+  }
+  hiprtcDestroyProgram(&prog);
+  if (!ok) {
+    if (c->module) (void)hipModuleUnload(c->module);
+    delete c;
+    if (g_log.empty()) g_log = "loading the compiled chain failed";
+    return NFAD_ECOMPILE;
+  }
+  c->live = true;
+  std::lock_guard<std::mutex> lock(g_mu);
+  if ((int)g_chains.size() >= kMaxChains) {
+    (void)hipModuleUnload(c->module);
+    delete c;
+    g_log = "too many compiled chains";
+    return NFAD_ECOMPILE;
+  }
+  c->name = "jit:" + std::to_string(g_chains.size());
+  g_chains.push_back(c);
+  *chain_id = NFAD_CHAIN_JIT_BASE + (int)g_chains.size() - 1;
+  return NFAD_OK;
+}
+
+// Copies the launch handles of a live chain out under the lock; nullptr if the id is dead.
+static const Compiled* find(int chain_id) {
+  std::lock_guard<std::mutex> lock(g_mu);
+  const int i = chain_id - NFAD_CHAIN_JIT_BASE;
+  if (i < 0 || i >= (int)g_chains.size() || !g_chains[i]->live) return nullptr;
+  return g_chains[i];
+}
+
+static int forward(const Compiled* c, const void* x, void* y, void* dydx, size_t n, int dtype, void* stream) {
+  const void* const in[1] = {x};
+  void* const out[2] = {y, dydx};
+  const int rc = validate<1, 2>(in, out, n, dtype);
+  if (rc != NFAD_OK || n == 0) return rc;
+  Ptrs<1, 2> p;
+  p.in[0] = x; p.out[0] = y; p.out[1] = dydx;
+  void* params[2] = {&p, &n};
+  const bool vec = all_aligned16(p);
+  const Geometry g = vec ? vec_geometry<1, 2>(n, dtype == NFAD_F32 ? 4 : 8) : scalar_geometry(n);
+  const hipError_t e = hipModuleLaunchKernel(vec ? c->vec[dtype] : c->scalar[dtype], g.grid, 1, 1, g.threads, 1, 1,
+                                             g.lds, reinterpret_cast<hipStream_t>(stream), params, nullptr);
+  return e == hipSuccess ? NFAD_OK : NFAD_ELAUNCH;
+}
+
+static const char* name_of(const Compiled* c) { return c->name.c_str(); }
+static const char* program_of(const Compiled* c) { return c->program.c_str(); }
+
+}  // namespace jit
+}  // namespace nfad
+
+extern "C" {
+
+int nfad_chain_compile(const char* program, int* chain_id) {
+  if (!program || !chain_id) return NFAD_ENULL;
+  return jit::compile(program, chain_id);
+}
+
+int nfad_chain_release(int chain_id) {
+  std::lock_guard<std::mutex> lock(jit::g_mu);
+  const int i = chain_id - NFAD_CHAIN_JIT_BASE;
+  if (i < 0 || i >= (int)jit::g_chains.size() || !jit::g_chains[i]->live) return NFAD_EINVAL_KIND;
+  jit::g_chains[i]->live = false;
+  (void)hipModuleUnload(jit::g_chains[i]->module);
+  jit::g_chains[i]->module = nullptr;
+  return NFAD_OK;
+}
+
+const char* nfad_chain_log(void) { return jit::g_log.c_str(); }
 
 }  // extern "C"

@@ -154,4 +154,18 @@ struct Erf {  // erf' = 2/sqrt(pi) exp(-v^2)
 };
 
 }  // namespace chain
+
+// Forward pass of a composed chain as a per-element operation of the streaming skeleton:
+// (x) -> (value, tangent) of Chain at the dual number (x, 1).              Sec. II-C eq. 3
+template <class Chain>
+struct ChainFwdOp {
+  static constexpr int kIn = 1, kOut = 2;
+  template <bool kWide>
+  __device__ __forceinline__ static void apply(const float (&in)[kIn], float (&out)[kOut]) {
+    const chain::Dual r = Chain::eval(chain::seed(in[0]));
+    out[0] = r.v;
+    out[1] = r.d;
+  }
+};
+
 }  // namespace nfad

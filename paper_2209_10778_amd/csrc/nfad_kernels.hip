@@ -276,6 +276,8 @@ const char* nfad_status_string(int status) {
     case NFAD_EALIGN: return "pointer not aligned to the element size";
     case NFAD_EALIAS: return "two outputs of one call coincide";
     case NFAD_ELAUNCH: return "HIP kernel launch failed";
+    case NFAD_EPROGRAM: return "malformed chain program";
+    case NFAD_ECOMPILE: return "run-time compilation of a chain failed";
   }
   return "unknown status";
 }

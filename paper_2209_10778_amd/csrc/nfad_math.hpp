@@ -27,7 +27,9 @@
 // y -> -0, dydx -> 0 as x -> -inf): an exponential that overflows to +inf only ever
 // reaches a reciprocal (1/inf = 0), never a product with zero.
 #pragma once
+#ifndef __HIPCC_RTC__
 #include <hip/hip_runtime.h>
+#endif
 
 namespace nfad {
 

@@ -22,7 +22,8 @@ def test_header_declares_the_expected_entry_points():
     assert declared_functions() == sorted([
         "nfad_fwd", "nfad_bwd", "nfad_recompute_fwd", "nfad_recompute_bwd", "nfad_saveall_num_saved",
         "nfad_saveall_fwd", "nfad_saveall_bwd", "nfad_status_string", "nfad_version",
-        "nfad_chain_count", "nfad_chain_name", "nfad_chain_program", "nfad_chain_fwd"])
+        "nfad_chain_count", "nfad_chain_name", "nfad_chain_program", "nfad_chain_fwd",
+        "nfad_chain_compile", "nfad_chain_release", "nfad_chain_log"])
 
 
 def test_library_exports_every_declared_symbol():
@@ -33,8 +34,8 @@ def test_library_exports_every_declared_symbol():
 
 def test_version_and_status_strings():
     assert nfad.nfad_version() >= 100
-    seen = {nfad.nfad_status_string(s) for s in range(7)}
-    assert len(seen) == 7 and all(seen)
+    seen = {nfad.nfad_status_string(s) for s in range(9)}
+    assert len(seen) == 9 and all(seen)
     assert nfad.nfad_status_string(0) == "ok"
     assert nfad.nfad_status_string(12345) == "unknown status"
 
@@ -73,6 +74,20 @@ def test_argument_validation_precedes_any_launch():
     assert L.nfad_saveall_fwd(5, A, A + 64, vpp(A, A, A, A), 4, 0, None) == EKIND
     assert L.nfad_saveall_bwd(1, A, vpp(A, A, None, None), A, 4, 0, None) == ENULL
     assert L.nfad_saveall_bwd(1, A, None, A, 0, 0, None) == OK
+
+
+def test_malformed_chain_programs_are_rejected_on_the_host():
+    """Parsing precedes any compiler or HIP call, so this runs without a GPU."""
+    L = nfad.lib()
+    cid = ctypes.c_int(-7)
+    for bad in (b"x x", b"x +", b"x foo", b"", b"1 2 +", b"x 1e999 *", b"x ; system", b"x nan *",
+                b" ".join([b"x"] * 200 + [b"+"] * 199)):
+        assert L.nfad_chain_compile(bad, ctypes.byref(cid)) == 7, bad
+        assert cid.value == -7 and nfad.nfad_chain_log()
+    assert L.nfad_chain_compile(None, ctypes.byref(cid)) == 3
+    assert L.nfad_chain_compile(b"x tanh", None) == 3
+    assert L.nfad_chain_release(5) == 1 and L.nfad_chain_release(1000 + 12345) == 1
+    assert nfad.nfad_chain_name(1000) is None or isinstance(nfad.nfad_chain_name(1000), str)
 
 
 def test_binding_rejects_host_tensors_and_mismatches():

@@ -81,3 +81,50 @@ def test_chain_errors_and_edges():
         nfad.nfad_chain_fwd(0, xd, y, d)
         compare(y, y_ref, torch.bfloat16, f"n={n}")
         compare(d, d_ref, torch.bfloat16, f"n={n}")
+
+
+# ------------------------------------------------------------------ run-time composed chains
+JIT_PROGRAMS = [
+    "x x * tanh",                               # tanh(x^2)
+    "x sigmoid x tanh *",                       # sigmoid(x) tanh(x)
+    "x 0.5 * exp 1 + log",                      # ln(1 + e^{x/2})
+    "x x softplus tanh *",                      # Mish again, compiled at run time
+    "x 1.702 x * sigmoid *",                    # the sigmoid approximation of GELU
+    "x erf x * 0.25 x * -",                     # x erf(x) - x/4
+    "1 x x * 1 + /",                            # 1/(1+x^2)
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_runtime_compiled_chains_match_interpreter(dtype):
+    td = DTYPES[dtype]
+    ids = []
+    for k, prog in enumerate(JIT_PROGRAMS):
+        cid = nfad.nfad_chain_compile(prog)
+        assert cid >= 1000 and nfad.nfad_chain_program(cid) == prog and nfad.nfad_chain_name(cid).startswith("jit:")
+        ids.append(cid)
+        a = inputs.gaussian(N, 2.0, 7300 + k)
+        x = inputs.to_storage(np.clip(a, -9.0, 9.0), dtype)
+        x64 = inputs.storage_to_f64(x)
+        y_ref, d_ref = chain.eval_chain(prog, x64)
+        xd = x.to(DEV)
+        y = torch.full_like(xd, float("nan"))
+        d = torch.full_like(xd, float("nan"))
+        nfad.nfad_chain_fwd(cid, xd, y, d)
+        rel = 2e-6 * np.maximum(1.0, np.abs(x64)) ** 2
+        compare(y, y_ref, td, f"jit {prog!r} y {dtype}", extra_tol=rel * np.maximum(1.0, np.abs(y_ref)))
+        compare(d, d_ref, td, f"jit {prog!r} dydx {dtype}", extra_tol=rel * np.maximum(1.0, np.abs(d_ref)))
+        # the scalar (misaligned) kernel of the same chain
+        buf = torch.zeros(N + 8, dtype=td, device=DEV)
+        buf[1:N + 1] = xd
+        y2, d2 = torch.empty_like(xd), torch.empty_like(xd)
+        nfad.nfad_chain_fwd(cid, buf[1:N + 1], y2, d2)
+        assert torch.equal(y2, y) and torch.equal(d2, d)
+    torch.cuda.synchronize()
+    for cid in ids:
+        nfad.nfad_chain_release(cid)
+        assert nfad.nfad_chain_name(cid) is None
+        with pytest.raises(nfad.NfadError):
+            nfad.nfad_chain_fwd(cid, xd, y, d)
+    with pytest.raises(nfad.NfadError):
+        nfad.nfad_chain_release(ids[0])
