@@ -1,0 +1,127 @@
+"""Training-memory footprint of an activation under the three regimes the paper compares
+(Sec. V-B, "maximum batch size"), on synthetic blocks shaped like BERT and ResNet-50 layers.
+
+No dataset or trained weight is involved: random weights, random inputs.  For one forward +
+backward pass of a block it reports the peak device memory above the resident weights and
+input, and the step time, for
+
+  composite : the activation written with framework primitives (the paper's baseline:
+              every primitive saves what its own backward needs)
+  native    : the framework's own fused activation (saves x)
+  saveall / recompute / fad : the libnfad kernels behind autograd Functions
+
+Run:  python -m paper_2209_10778_amd.footprint [--dtype bf16] [--batch 32]
+Prints one JSON line per (block, activation).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import time
+
+import torch
+import torch.nn as nn
+import torch.nn.functional as F
+
+from . import autograd as A
+
+_C = math.sqrt(2.0 / math.pi)
+COMPOSITE = {
+    "gelu_tanh": lambda x: 0.5 * x * (1.0 + torch.tanh(_C * (x + 0.044715 * x * x * x))),
+    "gelu_erf": lambda x: 0.5 * x * (1.0 + torch.erf(x * (1.0 / math.sqrt(2.0)))),
+    "swish": lambda x: x * torch.sigmoid(x),
+    "mish": lambda x: x * torch.tanh(F.softplus(x)),
+}
+NATIVE = {
+    "gelu_tanh": lambda x: F.gelu(x, approximate="tanh"),
+    "gelu_erf": lambda x: F.gelu(x),
+    "swish": F.silu,
+    "mish": F.mish,
+}
+
+
+class Act(nn.Module):
+    def __init__(self, kind, regime):
+        super().__init__()
+        self.kind, self.regime = kind, regime
+
+    def forward(self, x):
+        if self.regime == "composite":
+            return COMPOSITE[self.kind](x)
+        if self.regime == "native":
+            return NATIVE[self.kind](x)
+        return A.activation(x, self.kind, mode=self.regime)
+
+
+def bert_ffn(hidden, kind, regime):
+    return nn.Sequential(nn.Linear(hidden, 4 * hidden), Act(kind, regime), nn.Linear(4 * hidden, hidden))
+
+
+def resnet_bottleneck(cin, mid, kind, regime):
+    return nn.Sequential(
+        nn.Conv2d(cin, mid, 1, bias=False), nn.BatchNorm2d(mid), Act(kind, regime),
+        nn.Conv2d(mid, mid, 3, padding=1, bias=False), nn.BatchNorm2d(mid), Act(kind, regime),
+        nn.Conv2d(mid, cin, 1, bias=False), nn.BatchNorm2d(cin), Act(kind, regime))
+
+
+def measure(make_block, x, steps=5):
+    dev = x.device
+    torch.manual_seed(0)
+    block = make_block().to(device=dev, dtype=x.dtype)
+    x = x.clone().requires_grad_(True)
+    for _ in range(2):                                   # warm up allocator, autotuners
+        block(x).float().square().mean().backward()
+        block.zero_grad(set_to_none=True)
+        x.grad = None
+    torch.cuda.synchronize()
+    torch.cuda.reset_peak_memory_stats()
+    base = torch.cuda.memory_allocated()
+    y = block(x)
+    torch.cuda.synchronize()
+    held = torch.cuda.memory_allocated() - base          # kept alive for backward (incl. the output)
+    y.float().square().mean().backward()
+    torch.cuda.synchronize()
+    peak = torch.cuda.max_memory_allocated() - base
+    del y
+    block.zero_grad(set_to_none=True)
+    x.grad = None
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        block(x).float().square().mean().backward()
+        block.zero_grad(set_to_none=True)
+        x.grad = None
+    torch.cuda.synchronize()
+    return held, peak, (time.perf_counter() - t0) / steps * 1e3
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--dtype", default="bf16", choices=["f32", "f16", "bf16"])
+    ap.add_argument("--batch", type=int, default=32)
+    args = ap.parse_args()
+    td = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[args.dtype]
+    dev = torch.device("cuda:0")
+    torch.manual_seed(1)
+    cases = [
+        ("bert_base_ffn seq128", lambda k, r: (lambda: bert_ffn(768, k, r)),
+         torch.randn(args.batch * 128, 768, device=dev, dtype=td), ("gelu_tanh", "gelu_erf")),
+        ("resnet50_bottleneck 56x56", lambda k, r: (lambda: resnet_bottleneck(256, 64, k, r)),
+         torch.randn(args.batch, 256, 56, 56, device=dev, dtype=td), ("swish", "mish", "gelu_tanh")),
+    ]
+    for name, maker, x, kinds in cases:
+        for kind in kinds:
+            row = {"block": name, "activation": kind, "dtype": args.dtype, "batch": args.batch, "regimes": {}}
+            for regime in ("composite", "native", "saveall", "recompute", "fad"):
+                held, peak, ms = measure(maker(kind, regime), x)
+                row["regimes"][regime] = {"held_after_fwd_MiB": round(held / 2 ** 20, 1),
+                                          "peak_MiB": round(peak / 2 ** 20, 1), "ms_per_step": round(ms, 3)}
+            r = row["regimes"]
+            row["held_composite_over_fad"] = round(r["composite"]["held_after_fwd_MiB"] / r["fad"]["held_after_fwd_MiB"], 3)
+            row["held_native_over_fad"] = round(r["native"]["held_after_fwd_MiB"] / r["fad"]["held_after_fwd_MiB"], 3)
+            row["time_recompute_over_fad"] = round(r["recompute"]["ms_per_step"] / r["fad"]["ms_per_step"], 3)
+            print(json.dumps(row), flush=True)
+
+
+if __name__ == "__main__":
+    main()

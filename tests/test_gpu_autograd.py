@@ -1,0 +1,77 @@
+"""The autograd front end: values and input gradients against the oracle, and what it saves."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import chain as ochain
+import paper_2209_10778_amd as nfad
+from paper_2209_10778_amd import autograd as A
+from paper_2209_10778_amd import inputs
+from parity import compare, tolerance
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+KIND = {"gelu_tanh": 0, "gelu_erf": 1, "swish": 2, "mish": 3}
+
+
+@pytest.mark.parametrize("mode", ["fad", "recompute", "saveall"])
+@pytest.mark.parametrize("name", sorted(KIND))
+def test_value_and_gradient(name, mode):
+    shape = (7, 33, 129)
+    n = int(np.prod(shape))
+    x = inputs.to_storage(inputs.gaussian(n, 1.5, 8100 + KIND[name]), "f32")
+    gy = inputs.to_storage(inputs.gaussian(n, 1.0, 8200 + KIND[name]), "f32")
+    x64, gy64 = inputs.storage_to_f64(x), inputs.storage_to_f64(gy)
+    y_ref, d_ref = oracle.fwd(KIND[name], x64)
+    xd = x.to(DEV).view(shape).requires_grad_(True)
+    y = A.activation(xd, name, mode=mode)
+    assert y.shape == xd.shape
+    y.backward(gy.to(DEV).view(shape))
+    compare(y.detach(), y_ref, torch.float32, f"{name} {mode} y")
+    g_ref = gy64 * d_ref
+    tol = np.abs(gy64) * 4e-6 * np.maximum(1.0, np.abs(x64))
+    compare(xd.grad, g_ref, torch.float32, f"{name} {mode} grad", extra_tol=tol)
+
+
+def test_only_one_tensor_is_saved_by_fad():
+    x = torch.randn(1 << 16, device=DEV, requires_grad=True)
+    for name in KIND:
+        y = A.activation(x, name)
+        saved = y.grad_fn.saved_tensors
+        assert len(saved) == 1 and saved[0].data_ptr() != x.data_ptr()      # dydx, not x
+        k = nfad.nfad_saveall_num_saved(KIND[name])
+        ys = A.activation(x, name, mode="saveall")
+        assert len(ys.grad_fn.saved_tensors) == k
+        yr = A.activation(x, name, mode="recompute")
+        rec = yr.grad_fn.saved_tensors
+        assert len(rec) == 1 and rec[0].data_ptr() == x.data_ptr()          # x itself
+
+
+def test_chain_front_end_builtin_and_compiled():
+    n = 50_001
+    x = inputs.to_storage(np.clip(inputs.gaussian(n, 2.0, 8300), -9, 9), "f32")
+    x64 = inputs.storage_to_f64(x)
+    for spec, prog in (("tanhshrink", "x x tanh -"), ("x sigmoid x tanh *", "x sigmoid x tanh *")):
+        xd = x.to(DEV).requires_grad_(True)
+        y = A.chain(xd, spec)
+        y.sum().backward()
+        y_ref, d_ref = ochain.eval_chain(prog, x64)
+        rel = 2e-6 * np.maximum(1.0, np.abs(x64))
+        compare(y.detach(), y_ref, torch.float32, f"chain {spec} y", extra_tol=rel * np.maximum(1, np.abs(y_ref)))
+        compare(xd.grad, d_ref, torch.float32, f"chain {spec} grad", extra_tol=rel * np.maximum(1, np.abs(d_ref)))
+
+
+def test_module_in_a_small_network_trains_a_step():
+    torch.manual_seed(0)
+    net = torch.nn.Sequential(torch.nn.Linear(64, 256), A.Activation("mish"), torch.nn.Linear(256, 8)).to(DEV)
+    x = torch.randn(32, 64, device=DEV)
+    loss = net(x).square().mean()
+    loss.backward()
+    assert all(p.grad is not None and bool(torch.isfinite(p.grad).all()) for p in net.parameters())
+    # same network with torch's own Mish gives the same gradients to fp32 accuracy
+    ref = torch.nn.Sequential(torch.nn.Linear(64, 256), torch.nn.Mish(), torch.nn.Linear(256, 8)).to(DEV)
+    ref.load_state_dict({k.replace("1.", "1."): v for k, v in net.state_dict().items()})
+    ref(x).square().mean().backward()
+    for p, q in zip(net.parameters(), ref.parameters()):
+        assert torch.allclose(p.grad, q.grad, rtol=2e-4, atol=2e-6)
