@@ -1,0 +1,233 @@
+"""Automatic detection and fusion of forward-AD chains in imperative PyTorch code.
+
+The paper finds fad chains in PyTorch's dynamic graph with a finite state machine over
+tensor-operator pairs (Sec. IV-A): an input tensor is fad (Y, produced by a fad operator)
+or not (N), an operator is fad (Y) or not (N), which gives the four forward states
+
+    NN  ordinary execution            NY  a chain begins
+    YY  the chain continues           YN  the chain ends
+
+and the chain between NY and YN is an R^1 -> R^M element-wise function whose backward pass
+needs one saved tensor per output (Sec. IV-B).  The paper executes every operator eagerly and
+computes tangents beside it; on MI355X the better move is not to execute the chain's
+operators at all: inside `with fuse():` a fad operator applied to a tensor returns a LAZY
+tensor that only records the chain (as a postfix program over the primitives), each further
+fad operator extends the record (YY), and the first non-fad use (YN) compiles the whole chain
+into ONE fused forward kernel (nfad_chain_compile, cached per program) that writes y and
+dydx; backward is one multiply.  Intermediates never exist, so there is nothing to release.
+
+A binary operator is fad only if both operands derive from the same source tensor, or one
+of them is a Python number (Sec. III-A); otherwise it is an nfad operator and ends the chain.
+A lazy tensor used by several consumers is materialised once per distinct chain (M outputs).
+
+    from paper_2209_10778_amd import trace
+    with trace.fuse() as t:
+        y = x * torch.tanh(torch.nn.functional.softplus(x))     # user-written Mish
+        z = torch.relu(y)                                        # non-fad use: chain ends here
+    t.states   -> ['NY', 'YY', 'YY', 'YN']
+"""
+from __future__ import annotations
+
+import math
+from typing import List, Optional
+
+import torch
+import torch.nn.functional as F
+from torch.overrides import TorchFunctionMode
+
+from . import autograd as A
+
+SUPPORTED_DTYPES = (torch.float32, torch.float16, torch.bfloat16)
+
+
+def classify(input_is_fad: bool, op_is_fad: bool) -> str:
+    """Forward state of a tensor-operator pair (Sec. IV-A)."""
+    return ("Y" if input_is_fad else "N") + ("Y" if op_is_fad else "N")
+
+
+class Lazy(torch.Tensor):
+    """A fad tensor: the not-yet-executed chain `program` applied to `source`."""
+
+    @staticmethod
+    def __new__(cls, source: torch.Tensor, program: List[str], tracer: "fuse"):
+        r = torch.Tensor._make_wrapper_subclass(cls, source.shape, dtype=source.dtype, device=source.device,
+                                                requires_grad=source.requires_grad)
+        r._source, r._program, r._tracer, r._value = source, list(program), tracer, None
+        return r
+
+    def materialize(self) -> torch.Tensor:
+        """YN: run the fused forward kernel of the recorded chain; keeps only dydx for backward."""
+        if self._value is None:
+            self._value = A.chain(self._source, " ".join(self._program))
+            self._tracer.kernels.append(" ".join(self._program))
+        return self._value
+
+    def __repr__(self):
+        return f"Lazy(chain={' '.join(self._program)!r}, shape={tuple(self.shape)})"
+
+    @classmethod
+    def __torch_dispatch__(cls, func, types, args=(), kwargs=None):
+        # never reached: every operator on a Lazy is resolved at the torch-function level below
+        raise RuntimeError(f"{func} reached a lazy chain tensor that was not materialised")
+
+    @classmethod
+    def __torch_function__(cls, func, types, args=(), kwargs=None):
+        kwargs = kwargs or {}
+        lazies = [a for a in _flatten(args) + _flatten(tuple(kwargs.values())) if isinstance(a, Lazy)]
+        return lazies[0]._tracer._dispatch(func, args, kwargs)
+
+
+def _flatten(xs):
+    out = []
+    for a in xs:
+        if isinstance(a, (list, tuple)):
+            out += _flatten(a)
+        else:
+            out.append(a)
+    return out
+
+
+def _const(v) -> Optional[str]:
+    if isinstance(v, bool) or not isinstance(v, (int, float)):
+        return None
+    return repr(float(v)) if math.isfinite(float(v)) else None
+
+
+# fad operators: name -> (arity, builder over operand programs)
+def _un(tok):
+    return lambda a: a + [tok]
+
+
+def _bin(tok):
+    return lambda a, b: a + b + [tok]
+
+
+_UNARY = {
+    "neg": _un("neg"), "exp": _un("exp"), "log": _un("log"), "tanh": _un("tanh"), "sigmoid": _un("sigmoid"),
+    "softplus": _un("softplus"), "erf": _un("erf"),
+    "square": lambda a: a + a + ["*"],
+    "silu": lambda a: a + a + ["sigmoid", "*"],
+    "mish": lambda a: a + a + ["softplus", "tanh", "*"],
+    "gelu_erf": lambda a: ["0.5"] + a + ["*", "1", repr(1.0 / math.sqrt(2.0))] + a + ["*", "erf", "+", "*"],
+    "gelu_tanh": lambda a: ["0.5"] + a + ["*", "1", repr(math.sqrt(2.0 / math.pi))] + a + ["0.044715"] + a + a
+    + ["*"] + a + ["*", "*", "+", "*", "tanh", "+", "*"],
+}
+_BINARY = {"add": _bin("+"), "sub": _bin("-"), "mul": _bin("*"), "div": _bin("/")}
+
+
+def _op_name(func):
+    n = getattr(func, "__name__", "")
+    table = {
+        "add": "add", "__add__": "add", "__radd__": "radd", "sub": "sub", "__sub__": "sub", "__rsub__": "rsub",
+        "rsub": "rsub", "mul": "mul", "__mul__": "mul", "__rmul__": "rmul", "multiply": "mul",
+        "div": "div", "true_divide": "div", "__truediv__": "div", "__rtruediv__": "rdiv", "__rdiv__": "rdiv", "__div__": "div", "divide": "div",
+        "neg": "neg", "negative": "neg", "__neg__": "neg", "exp": "exp", "log": "log", "tanh": "tanh",
+        "sigmoid": "sigmoid", "softplus": "softplus", "erf": "erf", "square": "square", "silu": "silu",
+        "mish": "mish", "gelu": "gelu", "pow": "pow", "__pow__": "pow",
+    }
+    return table.get(n)
+
+
+class fuse(TorchFunctionMode):
+    """Context manager: detect fad chains and run each as one fused kernel."""
+
+    def __init__(self, require_cuda: bool = True):
+        super().__init__()
+        self.require_cuda = require_cuda   # False only lets chains be RECORDED on host tensors (tests)
+        self.states: List[str] = []      # forward state of every tensor-operator pair seen
+        self.kernels: List[str] = []     # chain programs that were materialised, in order
+
+    # ---- operand analysis
+    def _operand(self, a, source):
+        """Program of operand `a` relative to `source`, or None if it is not fad there."""
+        if isinstance(a, Lazy):
+            return a._program if a._source is source else None
+        if isinstance(a, torch.Tensor):
+            return ["x"] if a is source else None
+        c = _const(a)
+        return [c] if c is not None else None
+
+    def _eligible(self, t) -> bool:
+        return (isinstance(t, torch.Tensor) and not isinstance(t, Lazy) and (t.is_cuda or not self.require_cuda)
+                and t.dtype in SUPPORTED_DTYPES and t.dim() > 0)
+
+    def _try_fad(self, func, args, kwargs):
+        """Returns a Lazy if (func, args) is a fad tensor-operator pair, else None."""
+        op = _op_name(func)
+        if op is None:
+            return None
+        tensors = [a for a in args if isinstance(a, torch.Tensor)]
+        if not tensors:
+            return None
+        lazies = [a for a in tensors if isinstance(a, Lazy)]
+        source = lazies[0]._source if lazies else tensors[0]
+        if not lazies and not self._eligible(source):
+            return None
+        prog = None
+        if op == "gelu":
+            approx = kwargs.get("approximate", "none")
+            if len(args) == 1 and set(kwargs) <= {"approximate"}:
+                a = self._operand(args[0], source)
+                prog = None if a is None else _UNARY["gelu_tanh" if approx == "tanh" else "gelu_erf"](a)
+        elif op == "softplus":
+            if len(args) == 1 and kwargs.get("beta", 1.0) == 1.0 and kwargs.get("threshold", 20.0) == 20.0:
+                a = self._operand(args[0], source)
+                prog = None if a is None else _UNARY["softplus"](a)
+        elif op == "pow":
+            if len(args) == 2 and not kwargs and isinstance(args[1], int) and not isinstance(args[1], bool) \
+                    and 2 <= args[1] <= 8:
+                a = self._operand(args[0], source)
+                if a is not None:
+                    prog = list(a)
+                    for _ in range(args[1] - 1):
+                        prog = prog + a + ["*"]
+        elif op in _UNARY:
+            if len(args) == 1 and (not kwargs or kwargs == {"inplace": False}):
+                a = self._operand(args[0], source)
+                prog = None if a is None else _UNARY[op](a)
+        else:
+            base = {"radd": "add", "rsub": "sub", "rmul": "mul", "rdiv": "div"}.get(op, op)
+            if len(args) == 2 and (not kwargs or (base in ("add", "sub") and kwargs == {"alpha": 1})):
+                l, r = (args[1], args[0]) if op in ("rsub", "rdiv") else (args[0], args[1])
+                a, b = self._operand(l, source), self._operand(r, source)
+                same_shape = all(t.shape == source.shape for t in tensors)
+                if a is not None and b is not None and same_shape:
+                    prog = _BINARY[base](a, b)
+        if prog is None or "x" not in prog or len(prog) > 250:
+            return None
+        return Lazy(source, prog, self)
+
+    # ---- the state machine
+    def _dispatch(self, func, args, kwargs):
+        if getattr(func, "__name__", "") in _PASSIVE:          # attribute reads: not graph operators
+            with torch._C.DisableTorchFunctionSubclass():
+                return func(*args, **kwargs)
+        with torch._C.DisableTorchFunctionSubclass():
+            return self._step(func, args, kwargs)
+
+    def _step(self, func, args, kwargs):
+        flat = _flatten(args) + _flatten(tuple(kwargs.values()))
+        input_is_fad = any(isinstance(a, Lazy) for a in flat)
+        has_tensor = any(isinstance(a, torch.Tensor) for a in flat)
+        lazy = self._try_fad(func, args, kwargs) if has_tensor else None
+        if has_tensor:
+            self.states.append(classify(input_is_fad, lazy is not None))
+        if lazy is not None:                       # NY or YY: record, execute nothing
+            return lazy
+        if input_is_fad:                           # YN: the chain ends; fuse it, then run the operator
+            args = _map(args, lambda a: a.materialize() if isinstance(a, Lazy) else a)
+            kwargs = {k: _map((v,), lambda a: a.materialize() if isinstance(a, Lazy) else a)[0]
+                      for k, v in kwargs.items()}
+        return func(*args, **kwargs)               # NN (or the operator after YN)
+
+    def __torch_function__(self, func, types, args=(), kwargs=None):
+        return self._dispatch(func, args, kwargs or {})
+
+
+# attribute reads and bookkeeping calls that are not operators of the graph
+_PASSIVE = {"__get__", "__set__", "size", "dim", "stride", "is_contiguous", "numel", "__len__", "__repr__",
+            "is_floating_point", "type", "data_ptr", "requires_grad_", "_make_wrapper_subclass", "detach"}
+
+
+def _map(xs, f):
+    return type(xs)(_map(a, f) if isinstance(a, (list, tuple)) else f(a) for a in xs)

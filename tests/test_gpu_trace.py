@@ -1,0 +1,116 @@
+"""The chain detector end to end on the GPU: user-written PyTorch activations are fused into one
+forward kernel each, values and gradients match the oracle, and one tensor is saved."""
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+import oracle
+from oracle import chain as ochain
+from paper_2209_10778_amd import inputs, trace
+from parity import compare
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def active(states):
+    return [s for s in states if s != "NN"]
+
+
+def _x(n, seed, dtype="f32"):
+    return inputs.to_storage(np.clip(inputs.gaussian(n, 2.0, seed), -9, 9), dtype)
+
+
+USER_CODE = {
+    "mish": (lambda x: x * torch.tanh(F.softplus(x)), oracle.MISH, "x x softplus tanh *"),
+    "swish": (lambda x: x * torch.sigmoid(x), oracle.SWISH, "x x sigmoid *"),
+    "gelu_tanh": (lambda x: 0.5 * x * (1.0 + torch.tanh(0.7978845608028654 * (x + 0.044715 * x ** 3))),
+                  oracle.GELU_TANH, None),
+    "gelu_erf": (lambda x: x * 0.5 * (1.0 + torch.erf(x / 1.4142135623730951)), oracle.GELU_ERF, None),
+}
+
+
+@pytest.mark.parametrize("name", sorted(USER_CODE))
+def test_user_written_activation_is_fused_and_correct(name):
+    fn, kind, program = USER_CODE[name]
+    n = 70_001
+    x = _x(n, 9000 + kind)
+    gy = inputs.to_storage(inputs.gaussian(n, 1.0, 9100 + kind), "f32")
+    x64, gy64 = inputs.storage_to_f64(x), inputs.storage_to_f64(gy)
+    xd = x.to(DEV).requires_grad_(True)
+    with trace.fuse() as t:
+        y = fn(xd)
+        assert isinstance(y, trace.Lazy) and t.kernels == []       # nothing executed yet
+        z = y.reshape(-1)                                          # non-fad use: the chain ends (YN)
+    assert len(t.kernels) == 1 and (program is None or t.kernels[0] == program)
+    # one or more branches begin at the source (NY), continue and merge (YY), and the chain ends once (YN)
+    st = active(t.states)
+    assert st[0] == "NY" and st[-1] == "YN" and set(st[1:-1]) <= {"NY", "YY"} and st.count("YN") == 1
+    saved = z.grad_fn.next_functions[0][0].saved_tensors if z.grad_fn.name() != "_FadChainBackward" else z.grad_fn.saved_tensors
+    assert len(saved) == 1                                          # dydx only
+    z.backward(gy.to(DEV))
+    y_ref, d_ref = oracle.fwd(kind, x64)
+    rel = 2e-6 * np.maximum(1.0, np.abs(x64))
+    compare(z.detach(), y_ref, torch.float32, f"traced {name} y", extra_tol=rel * np.maximum(1, np.abs(y_ref)))
+    compare(xd.grad, gy64 * d_ref, torch.float32, f"traced {name} grad",
+            extra_tol=np.abs(gy64) * rel * np.maximum(1, np.abs(d_ref)) * 2)
+
+
+def test_chain_resolves_after_the_context_has_closed():
+    x = _x(10_000, 9200).to(DEV).requires_grad_(True)
+    with trace.fuse() as t:
+        y = F.silu(x)
+    assert isinstance(y, trace.Lazy) and t.kernels == []
+    loss = y.sum()                    # outside the context: still resolves through the recorded chain
+    loss.backward()
+    assert t.kernels == ["x x sigmoid *"]
+    _, d_ref = oracle.fwd(oracle.SWISH, inputs.storage_to_f64(x.detach().cpu()))
+    compare(x.grad, d_ref, torch.float32, "late resolve grad", extra_tol=4e-6 * np.maximum(1, np.abs(d_ref)))
+
+
+def test_two_consumers_of_one_source_give_two_outputs():
+    """R^1 -> R^M: one source, two chains ending in different non-fad operators."""
+    x = _x(20_000, 9300).to(DEV).requires_grad_(True)
+    x64 = inputs.storage_to_f64(x.detach().cpu())
+    with trace.fuse() as t:
+        h = torch.tanh(x)             # shared prefix
+        a = (h * x).sum()             # chain 1: x tanh x *
+        b = torch.sigmoid(h).sum()    # chain 2: x tanh sigmoid
+    (a + b).backward()
+    assert sorted(t.kernels) == sorted(["x tanh x *", "x tanh sigmoid"])
+    _, d1 = ochain.eval_chain("x tanh x *", x64)
+    _, d2 = ochain.eval_chain("x tanh sigmoid", x64)
+    compare(x.grad, d1 + d2, torch.float32, "merged tangents", extra_tol=1e-5 * np.maximum(1, np.abs(x64)))
+
+
+def test_mixing_sources_ends_both_chains():
+    x = _x(5_000, 9400).to(DEV)
+    w = _x(5_000, 9401).to(DEV)
+    with trace.fuse() as t:
+        y = torch.tanh(x) * torch.sigmoid(w)     # operands from different sources: nfad operator
+    assert not isinstance(y, trace.Lazy)
+    assert sorted(t.kernels) == ["x sigmoid", "x tanh"]
+    ref = np.tanh(inputs.storage_to_f64(x.cpu())) * (1 / (1 + np.exp(-inputs.storage_to_f64(w.cpu()))))
+    compare(y, ref, torch.float32, "mixed sources", extra_tol=1e-6)
+
+
+def test_a_small_network_with_user_written_mish_trains_a_step():
+    torch.manual_seed(0)
+    lin1, lin2 = torch.nn.Linear(64, 256).to(DEV), torch.nn.Linear(256, 8).to(DEV)
+    x = torch.randn(32, 64, device=DEV)
+
+    def net(v):
+        h = lin1(v)
+        return lin2(h * torch.tanh(F.softplus(h)))
+
+    with trace.fuse() as t:
+        net(x).square().mean().backward()
+    assert t.kernels == ["x x softplus tanh *", "x x *"]      # the activation, and the loss's square
+    g1 = [p.grad.clone() for p in list(lin1.parameters()) + list(lin2.parameters())]
+    for p in list(lin1.parameters()) + list(lin2.parameters()):
+        p.grad = None
+    net(x).square().mean().backward()              # plain PyTorch, no fusion
+    g2 = [p.grad for p in list(lin1.parameters()) + list(lin2.parameters())]
+    for a, b in zip(g1, g2):
+        assert torch.allclose(a, b, rtol=2e-4, atol=2e-6)

@@ -1,0 +1,85 @@
+"""The chain detector's state machine and program builder, on host tensors (recording only:
+nothing is executed, and materialising a chain on the host must fail loudly)."""
+import pytest
+import torch
+import torch.nn.functional as F
+
+from oracle import chain as ochain
+from paper_2209_10778_amd import trace
+
+
+def test_classify_is_the_papers_four_states():
+    assert [trace.classify(a, b) for a in (False, True) for b in (False, True)] == ["NN", "NY", "YN", "YY"]
+
+
+def active(states):
+    return [s for s in states if s != "NN"]
+
+
+def test_user_written_mish_is_one_chain():
+    x = torch.randn(5, 7)
+    with trace.fuse(require_cuda=False) as t:
+        y = x * torch.tanh(F.softplus(x))
+    assert isinstance(y, trace.Lazy) and y.shape == x.shape and y.dtype == x.dtype
+    assert " ".join(y._program) == "x x softplus tanh *"
+    assert active(t.states) == ["NY", "YY", "YY"]          # softplus begins, tanh and mul continue
+    assert t.kernels == []                                  # nothing has run
+
+
+def test_user_written_gelu_tanh_program_evaluates_to_gelu():
+    import numpy as np
+    import oracle
+    x = torch.randn(64)
+    with trace.fuse(require_cuda=False):
+        y = 0.5 * x * (1.0 + torch.tanh(0.7978845608028654 * (x + 0.044715 * x ** 3)))
+    prog = " ".join(y._program)
+    xs = np.linspace(-6, 6, 241)
+    v, d = ochain.eval_chain(prog, xs)
+    vr, dr = oracle.fwd(oracle.GELU_TANH, xs)
+    assert np.max(np.abs(v - vr)) < 1e-13 and np.max(np.abs(d - dr)) < 1e-13
+
+
+def test_builtin_functionals_expand_to_primitives():
+    x = torch.randn(8)
+    with trace.fuse(require_cuda=False):
+        progs = {
+            "silu": " ".join(F.silu(x)._program),
+            "mish": " ".join(F.mish(x)._program),
+            "square": " ".join(torch.square(x)._program),
+            "rsub": " ".join((1 - x)._program),
+            "rdiv": " ".join((2 / x)._program),
+            "neg": " ".join((-x)._program),
+            "sigmoid_method": " ".join(x.sigmoid()._program),
+        }
+    assert progs == {"silu": "x x sigmoid *", "mish": "x x softplus tanh *", "square": "x x *",
+                     "rsub": "1.0 x -", "rdiv": "2.0 x /", "neg": "x neg", "sigmoid_method": "x sigmoid"}
+
+
+def test_binary_operator_needs_the_same_source():
+    x, w = torch.randn(4, 4), torch.randn(4, 4)
+    with trace.fuse(require_cuda=False) as t:
+        a = torch.tanh(x)                 # NY
+        b = torch.sigmoid(w)              # NY (another chain, another source)
+        assert isinstance(a, trace.Lazy) and isinstance(b, trace.Lazy) and a._source is x and b._source is w
+        with pytest.raises((ValueError, RuntimeError, ImportError)):
+            a * b                         # different sources: nfad operator, YN; materialising on the host fails
+    assert active(t.states)[:3] == ["NY", "NY", "YN"]
+
+
+def test_non_fad_operator_is_passed_through_untouched():
+    x = torch.randn(3, 3)
+    with trace.fuse(require_cuda=False) as t:
+        y = torch.relu(x) @ x             # neither is a fad primitive
+    assert not isinstance(y, trace.Lazy) and active(t.states) == []
+    assert torch.equal(y, torch.relu(x) @ x)
+
+
+def test_unsupported_variants_do_not_start_a_chain():
+    x = torch.randn(6)
+    xi = torch.arange(6)
+    with trace.fuse(require_cuda=False):
+        assert not isinstance(F.softplus(x, beta=2.0), trace.Lazy)
+        assert not isinstance(torch.tanh(xi.double()), trace.Lazy)      # float64 is not a storage type here
+        assert not isinstance(x ** 2.5, trace.Lazy)
+        assert not isinstance(x + torch.randn(1), trace.Lazy)           # broadcasting a different tensor
+        assert isinstance(x ** 2, trace.Lazy)
