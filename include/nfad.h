@@ -70,6 +70,7 @@ typedef enum {
 } nfad_status_t;
 
 #define NFAD_MAX_SAVED 4
+#define NFAD_MAX_OUTPUTS 4
 
 /* Forward pass of the method (Sec. II-C eq. 3): y[i] = f(x[i]), dydx[i] = f'(x[i]).
  * x: in, n elements.  y, dydx: out, n elements each.  dydx is the only tensor the
@@ -139,6 +140,28 @@ int nfad_chain_fwd(int chain_id, const void* x, void* y, void* dydx, size_t n, i
 int nfad_chain_compile(const char* program, int* chain_id);
 int nfad_chain_release(int chain_id);
 const char* nfad_chain_log(void);
+
+/* One source, several outputs (Sec. II-D "R^1 -> R^M", Sec. IV-A): m chains over the same x,
+ * 1 <= m <= NFAD_MAX_OUTPUTS, fused into ONE forward kernel that reads x once and writes
+ * y[j] and dydx[j] for j < m (one saved tangent per output); the backward pass merges the
+ * m upstream gradients at the source, gx[i] = sum_j gy[j][i] * dydx[j][i].
+ *   nfad_chain_compile_multi  `programs` = host array of m postfix programs; errors as
+ *                             nfad_chain_compile, NFAD_EINVAL_KIND for a bad m.  The id
+ *                             works with nfad_chain_fwd_multi / _release / _name;
+ *                             nfad_chain_program returns the programs joined by " ; "
+ *   nfad_chain_num_outputs    m of a run-time compiled chain, 1 for a built-in chain, -1 for
+ *                             a bad id
+ *   nfad_chain_fwd_multi      y, dydx: host arrays of m device pointers (all 2m outputs
+ *                             distinct).  nfad_chain_fwd on an id with m > 1, or this call
+ *                             on a built-in id, gives NFAD_EINVAL_KIND
+ *   nfad_bwd_multi            gy, dydx: host arrays of m device pointers; gx may coincide
+ *                             with any input */
+int nfad_chain_compile_multi(const char* const* programs, int m, int* chain_id);
+int nfad_chain_num_outputs(int chain_id);
+int nfad_chain_fwd_multi(int chain_id, const void* x, void* const* y, void* const* dydx, size_t n,
+                         int dtype, void* stream);
+int nfad_bwd_multi(const void* const* gy, const void* const* dydx, int m, void* gx, size_t n,
+                   int dtype, void* stream);
 
 /* Static, NUL-terminated description of a status code (never NULL). */
 const char* nfad_status_string(int status);

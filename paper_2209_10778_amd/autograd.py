@@ -117,6 +117,36 @@ def chain(x: torch.Tensor, chain) -> torch.Tensor:
     return _FadChain.apply(x, _chain_id(chain))
 
 
+class _FadChainMulti(torch.autograd.Function):
+    """One source, M chains: one kernel reads x once and writes M values and M tangents;
+    backward merges the M upstream gradients at the source."""
+
+    @staticmethod
+    def forward(ctx, x, chain_id, m):
+        xf = _flat(x)
+        ys = [torch.empty_like(xf) for _ in range(m)]
+        ds = [torch.empty_like(xf) for _ in range(m)]
+        B.nfad_chain_fwd_multi(chain_id, xf, ys, ds)
+        ctx.save_for_backward(*ds)
+        return tuple(y.view(x.shape) for y in ys)
+
+    @staticmethod
+    def backward(ctx, *gys):
+        ds = list(ctx.saved_tensors)
+        gyf = [_flat(g) for g in gys]
+        gx = torch.empty_like(gyf[0])
+        B.nfad_bwd_multi(gyf, ds, gx)
+        return gx.view(gys[0].shape), None, None
+
+
+def chain_multi(x: torch.Tensor, programs):
+    """Several chains over the same source, fused into one forward kernel (R^1 -> R^M)."""
+    key = tuple(programs)
+    if key not in _compiled:
+        _compiled[key] = B.nfad_chain_compile_multi(list(programs))
+    return _FadChainMulti.apply(x, _compiled[key], len(programs))
+
+
 _compiled: dict = {}
 
 

@@ -54,12 +54,18 @@ def lib() -> ctypes.CDLL:
         L.nfad_chain_program.restype = ctypes.c_char_p
         L.nfad_chain_compile.argtypes = [ctypes.c_char_p, ctypes.POINTER(ci)]
         L.nfad_chain_release.argtypes = [ci]
+        L.nfad_chain_compile_multi.argtypes = [ctypes.POINTER(ctypes.c_char_p), ci, ctypes.POINTER(ci)]
+        L.nfad_chain_num_outputs.argtypes = [ci]
+        L.nfad_chain_fwd_multi.argtypes = [ci, vp, vpp, vpp, sz, ci, vp]
+        L.nfad_bwd_multi.argtypes = [vpp, vpp, ci, vp, sz, ci, vp]
         L.nfad_chain_log.restype = ctypes.c_char_p
         L.nfad_status_string.argtypes = [ci]
         L.nfad_status_string.restype = ctypes.c_char_p
         for name in ("nfad_fwd", "nfad_bwd", "nfad_recompute_fwd", "nfad_recompute_bwd",
                      "nfad_saveall_num_saved", "nfad_saveall_fwd", "nfad_saveall_bwd", "nfad_version",
-                     "nfad_chain_count", "nfad_chain_fwd", "nfad_chain_compile", "nfad_chain_release"):
+                     "nfad_chain_count", "nfad_chain_fwd", "nfad_chain_compile", "nfad_chain_release",
+                     "nfad_chain_compile_multi", "nfad_chain_num_outputs", "nfad_chain_fwd_multi",
+                     "nfad_bwd_multi"):
             getattr(L, name).restype = ci
         _lib = L
     return _lib
@@ -178,6 +184,34 @@ def nfad_chain_compile(program: str) -> int:
     if status != 0:
         raise NfadError(status, f"nfad_chain_compile({program!r}): {nfad_chain_log()}")
     return int(cid.value)
+
+
+def nfad_chain_compile_multi(programs) -> int:
+    """Compile m chains over the same source into ONE forward kernel; returns the chain id."""
+    arr = (ctypes.c_char_p * len(programs))(*[p.encode() for p in programs])
+    cid = ctypes.c_int(-1)
+    status = lib().nfad_chain_compile_multi(arr, len(programs), ctypes.byref(cid))
+    if status != 0:
+        raise NfadError(status, f"nfad_chain_compile_multi({list(programs)!r}): {nfad_chain_log()}")
+    return int(cid.value)
+
+
+def nfad_chain_num_outputs(chain_id: int) -> int:
+    return int(lib().nfad_chain_num_outputs(int(chain_id)))
+
+
+def nfad_chain_fwd_multi(chain_id, x, ys, dydxs, stream=None) -> None:
+    n, dt = _marshal(x, *ys, *dydxs)
+    _check(lib().nfad_chain_fwd_multi(int(chain_id), x.data_ptr(), _ptr_array(ys), _ptr_array(dydxs), n, dt,
+                                      _stream(stream)), "nfad_chain_fwd_multi")
+
+
+def nfad_bwd_multi(gys, dydxs, gx, stream=None) -> None:
+    if len(gys) != len(dydxs):
+        raise ValueError("one upstream gradient per saved tangent")
+    n, dt = _marshal(gx, *gys, *dydxs)
+    _check(lib().nfad_bwd_multi(_ptr_array(gys), _ptr_array(dydxs), len(gys), gx.data_ptr(), n, dt,
+                                _stream(stream)), "nfad_bwd_multi")
 
 
 def nfad_chain_release(chain_id: int) -> None:

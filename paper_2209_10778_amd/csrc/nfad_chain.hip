@@ -57,7 +57,9 @@ namespace nfad {
 namespace jit {
 struct Compiled;
 static const Compiled* find(int chain_id);
-static int forward(const Compiled* c, const void* x, void* y, void* dydx, size_t n, int dtype, void* stream);
+static int forward(const Compiled* c, const void* x, void* const* y, void* const* dydx, size_t n, int dtype,
+                   void* stream);
+static int outputs_of(const Compiled* c);
 static const char* name_of(const Compiled* c);
 static const char* program_of(const Compiled* c);
 }  // namespace jit
@@ -88,7 +90,10 @@ const char* nfad_chain_program(int chain_id) {
 int nfad_chain_fwd(int chain_id, const void* x, void* y, void* dydx, size_t n, int dtype, void* stream) {
   if (chain_id >= NFAD_CHAIN_JIT_BASE) {
     const jit::Compiled* c = jit::find(chain_id);
-    return c ? jit::forward(c, x, y, dydx, n, dtype, stream) : NFAD_EINVAL_KIND;
+    if (!c || jit::outputs_of(c) != 1) return NFAD_EINVAL_KIND;
+    void* const ys[1] = {y};
+    void* const ds[1] = {dydx};
+    return jit::forward(c, x, ys, ds, n, dtype, stream);
   }
   if (chain_id < 0 || chain_id >= kNumChains) return NFAD_EINVAL_KIND;
   const void* const in[1] = {x};
@@ -138,6 +143,7 @@ static constexpr int kMaxChains = 4096;
 
 struct Compiled {
   std::string program, name;
+  int m = 1;                                              // number of outputs (chains over the same x)
   hipModule_t module = nullptr;
   hipFunction_t vec[3] = {nullptr, nullptr, nullptr};     // indexed by nfad_dtype_t
   hipFunction_t scalar[3] = {nullptr, nullptr, nullptr};
@@ -148,7 +154,7 @@ static std::vector<Compiled*> g_chains;          // index = id - NFAD_CHAIN_JIT_
 static thread_local std::string g_log;
 
 // postfix program -> C++ type expression over nfad::chain templates (+ constant definitions)
-static bool translate(const char* program, std::string& consts, std::string& type, std::string& err) {
+static bool translate(const char* program, int index, std::string& consts, std::string& type, std::string& err) {
   static const struct { const char* tok; const char* tmpl; int arity; } kOps[] = {
       {"+", "Add", 2}, {"-", "Sub", 2}, {"*", "Mul", 2}, {"/", "Div", 2}, {"neg", "Neg", 1},
       {"exp", "Exp", 1}, {"log", "Log", 1}, {"tanh", "Tanh", 1}, {"sigmoid", "Sigmoid", 1},
@@ -184,9 +190,9 @@ static bool translate(const char* program, std::string& consts, std::string& typ
     const float c = strtof(tok.c_str(), &end);
     if (end == tok.c_str() || *end != '\0' || !isfinite(c)) { err = "unknown token '" + tok + "'"; return false; }
     char buf[96];
-    snprintf(buf, sizeof buf, "NFAD_CHAIN_CONSTANT(K%d, %af);\n", nconst, (double)c);  // exact hex-float literal
+    snprintf(buf, sizeof buf, "NFAD_CHAIN_CONSTANT(K%d_%d, %af);\n", index, nconst, (double)c);  // exact hex-float literal
     consts += buf;
-    stack.push_back("Const<K" + std::to_string(nconst) + ">");
+    stack.push_back("Const<K" + std::to_string(index) + "_" + std::to_string(nconst) + ">");
     ++nconst;
   }
   if (stack.size() != 1) { err = "program leaves " + std::to_string(stack.size()) + " values"; return false; }
@@ -197,14 +203,25 @@ static bool translate(const char* program, std::string& consts, std::string& typ
 
 static const char* kTypeNames[3] = {"float", "_Float16", "__bf16"};   // indexed by nfad_dtype_t
 
-static int compile(const char* program, int* chain_id) {
-  std::string consts, type, err;
+static int compile(const char* const* programs, int m, int* chain_id) {
+  std::string consts, aliases, list, joined, err;
   g_log.clear();
-  if (!translate(program, consts, type, err)) { g_log = err; return NFAD_EPROGRAM; }
+  for (int j = 0; j < m; ++j) {
+    std::string type;
+    if (!programs[j]) { g_log = "null program"; return NFAD_ENULL; }
+    if (!translate(programs[j], j, consts, type, err)) {
+      g_log = (m > 1 ? "program " + std::to_string(j) + ": " : std::string()) + err;
+      return NFAD_EPROGRAM;
+    }
+    aliases += "using UserChain" + std::to_string(j) + " = " + type + ";\n";
+    list += (j ? ", nfad::chain::UserChain" : "nfad::chain::UserChain") + std::to_string(j);
+    joined += (j ? " ; " : "") + std::string(programs[j]);
+  }
+  // m == 1 uses the same operation type as the built-in chains
+  const std::string op = m == 1 ? "nfad::ChainFwdOp<" + list + ">" : "nfad::ChainFwdMultiOp<" + list + ">";
 
   const std::string src = "#include \"nfad_stream_device.hpp\"\n#include \"nfad_chain.hpp\"\n"
-                          "namespace nfad { namespace chain {\n" + consts + "using UserChain = " + type +
-                          ";\n} }\n";
+                          "namespace nfad { namespace chain {\n" + consts + aliases + "} }\n";
   hiprtcProgram prog = nullptr;
   if (hiprtcCreateProgram(&prog, src.c_str(), "nfad_user_chain.hip", kNumEmbedded, const_cast<const char**>(kEmbeddedSources),
                           const_cast<const char**>(kEmbeddedNames)) != HIPRTC_SUCCESS) {
@@ -213,8 +230,8 @@ static int compile(const char* program, int* chain_id) {
   }
   std::string names[6];
   for (int t = 0; t < 3; ++t) {
-    names[t] = std::string("nfad::ew_vec_kernel<nfad::ChainFwdOp<nfad::chain::UserChain>, ") + kTypeNames[t] + ">";
-    names[3 + t] = std::string("nfad::ew_scalar_kernel<nfad::ChainFwdOp<nfad::chain::UserChain>, ") + kTypeNames[t] + ">";
+    names[t] = "nfad::ew_vec_kernel<" + op + ", " + kTypeNames[t] + ">";
+    names[3 + t] = "nfad::ew_scalar_kernel<" + op + ", " + kTypeNames[t] + ">";
   }
   for (auto& nm : names) hiprtcAddNameExpression(prog, nm.c_str());
 
@@ -241,7 +258,8 @@ static int compile(const char* program, int* chain_id) {
   hiprtcGetCode(prog, code.data());
 
   Compiled* c = new Compiled;
-  c->program = program;
+  c->program = joined;
+  c->m = m;
   bool ok = hipModuleLoadData(&c->module, code.data()) == hipSuccess;
   for (int t = 0; ok && t < 6; ++t) {
     const char* lowered = nullptr;
@@ -277,21 +295,40 @@ static const Compiled* find(int chain_id) {
   return g_chains[i];
 }
 
-static int forward(const Compiled* c, const void* x, void* y, void* dydx, size_t n, int dtype, void* stream) {
+template <int M>
+static int forward_m(const Compiled* c, const void* x, void* const* y, void* const* dydx, size_t n, int dtype,
+                     void* stream) {
   const void* const in[1] = {x};
-  void* const out[2] = {y, dydx};
-  const int rc = validate<1, 2>(in, out, n, dtype);
+  void* out[2 * M];
+  for (int j = 0; j < M; ++j) { out[2 * j] = y[j]; out[2 * j + 1] = dydx[j]; }
+  const int rc = validate<1, 2 * M>(in, out, n, dtype);
   if (rc != NFAD_OK || n == 0) return rc;
-  Ptrs<1, 2> p;
-  p.in[0] = x; p.out[0] = y; p.out[1] = dydx;
+  Ptrs<1, 2 * M> p;
+  p.in[0] = x;
+  for (int o = 0; o < 2 * M; ++o) p.out[o] = out[o];
   void* params[2] = {&p, &n};
   const bool vec = all_aligned16(p);
-  const Geometry g = vec ? vec_geometry<1, 2>(n, dtype == NFAD_F32 ? 4 : 8) : scalar_geometry(n);
+  const Geometry g = vec ? vec_geometry<1, 2 * M>(n, dtype == NFAD_F32 ? 4 : 8) : scalar_geometry(n);
   const hipError_t e = hipModuleLaunchKernel(vec ? c->vec[dtype] : c->scalar[dtype], g.grid, 1, 1, g.threads, 1, 1,
                                              g.lds, reinterpret_cast<hipStream_t>(stream), params, nullptr);
   return e == hipSuccess ? NFAD_OK : NFAD_ELAUNCH;
 }
 
+static int forward(const Compiled* c, const void* x, void* const* y, void* const* dydx, size_t n, int dtype,
+                   void* stream) {
+  if (!dtype_ok(dtype)) return NFAD_EINVAL_DTYPE;
+  if (n == 0) return NFAD_OK;
+  if (!y || !dydx) return NFAD_ENULL;
+  switch (c->m) {
+    case 1: return forward_m<1>(c, x, y, dydx, n, dtype, stream);
+    case 2: return forward_m<2>(c, x, y, dydx, n, dtype, stream);
+    case 3: return forward_m<3>(c, x, y, dydx, n, dtype, stream);
+    case 4: return forward_m<4>(c, x, y, dydx, n, dtype, stream);
+  }
+  return NFAD_EINVAL_KIND;
+}
+
+static int outputs_of(const Compiled* c) { return c->m; }
 static const char* name_of(const Compiled* c) { return c->name.c_str(); }
 static const char* program_of(const Compiled* c) { return c->program.c_str(); }
 
@@ -302,7 +339,29 @@ extern "C" {
 
 int nfad_chain_compile(const char* program, int* chain_id) {
   if (!program || !chain_id) return NFAD_ENULL;
-  return jit::compile(program, chain_id);
+  const char* const programs[1] = {program};
+  return jit::compile(programs, 1, chain_id);
+}
+
+int nfad_chain_compile_multi(const char* const* programs, int m, int* chain_id) {
+  if (!programs || !chain_id) return NFAD_ENULL;
+  if (m < 1 || m > NFAD_MAX_OUTPUTS) return NFAD_EINVAL_KIND;
+  return jit::compile(programs, m, chain_id);
+}
+
+int nfad_chain_num_outputs(int chain_id) {
+  if (chain_id >= NFAD_CHAIN_JIT_BASE) {
+    const jit::Compiled* c = jit::find(chain_id);
+    return c ? jit::outputs_of(c) : -1;
+  }
+  return (chain_id >= 0 && chain_id < kNumChains) ? 1 : -1;
+}
+
+int nfad_chain_fwd_multi(int chain_id, const void* x, void* const* y, void* const* dydx, size_t n, int dtype,
+                         void* stream) {
+  if (chain_id < NFAD_CHAIN_JIT_BASE) return NFAD_EINVAL_KIND;
+  const jit::Compiled* c = jit::find(chain_id);
+  return c ? jit::forward(c, x, y, dydx, n, dtype, stream) : NFAD_EINVAL_KIND;
 }
 
 int nfad_chain_release(int chain_id) {

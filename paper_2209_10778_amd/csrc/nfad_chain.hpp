@@ -168,4 +168,20 @@ struct ChainFwdOp {
   }
 };
 
+// One source element, M chains, 2M results: R^1 -> R^M with one saved tangent per output
+// (Sec. II-D "f: R^1 -> R^M", Sec. IV-A).  Output order: y0, dydx0, y1, dydx1, ...
+template <class... Chains>
+struct ChainFwdMultiOp {
+  static constexpr int kIn = 1, kOut = 2 * (int)sizeof...(Chains);
+  template <bool kWide>
+  __device__ __forceinline__ static void apply(const float (&in)[kIn], float (&out)[kOut]) {
+    const chain::Dual r[] = {Chains::eval(chain::seed(in[0]))...};
+#pragma unroll
+    for (int m = 0; m < (int)sizeof...(Chains); ++m) {
+      out[2 * m] = r[m].v;
+      out[2 * m + 1] = r[m].d;
+    }
+  }
+};
+
 }  // namespace nfad

@@ -29,6 +29,19 @@ struct BwdOp {
     out[0] = in[0] * in[1];
   }
 };
+// Backward pass of a chain with M outputs: the tangents of all consumers merge at the source,
+// gx = sum_m gy_m * dydx_m.  Inputs in the order gy0, dydx0, gy1, dydx1, ...        Sec. II-E, IV-B
+template <int M>
+struct BwdMultiOp {
+  static constexpr int kIn = 2 * M, kOut = 1;
+  template <bool kWide>
+  __device__ __forceinline__ static void apply(const float (&in)[kIn], float (&out)[kOut]) {
+    float acc = in[0] * in[1];
+#pragma unroll
+    for (int m = 1; m < M; ++m) acc = fma_(in[2 * m], in[2 * m + 1], acc);
+    out[0] = acc;
+  }
+};
 // Recomputation baseline: forward keeps nothing but x.               Sec. II-C "Recomputation"
 template <int KIND>
 struct RecomputeFwdOp {
@@ -184,6 +197,34 @@ int nfad_bwd(const void* gy, const void* dydx, void* gx, size_t n, int dtype, vo
   const void* const in[2] = {gy, dydx};
   void* const out[1] = {gx};
   return run<BwdOp>(dtype, in, out, n, stream);
+}
+
+int nfad_bwd_multi(const void* const* gy, const void* const* dydx, int m, void* gx, size_t n, int dtype,
+                   void* stream) {
+  if (m < 1 || m > NFAD_MAX_OUTPUTS) return NFAD_EINVAL_KIND;
+  if (!dtype_ok(dtype)) return NFAD_EINVAL_DTYPE;
+  if (n == 0) return NFAD_OK;
+  if (!gy || !dydx) return NFAD_ENULL;
+  void* const out[1] = {gx};
+  switch (m) {
+    case 1: {
+      const void* const in[2] = {gy[0], dydx[0]};
+      return run<BwdMultiOp<1>>(dtype, in, out, n, stream);
+    }
+    case 2: {
+      const void* const in[4] = {gy[0], dydx[0], gy[1], dydx[1]};
+      return run<BwdMultiOp<2>>(dtype, in, out, n, stream);
+    }
+    case 3: {
+      const void* const in[6] = {gy[0], dydx[0], gy[1], dydx[1], gy[2], dydx[2]};
+      return run<BwdMultiOp<3>>(dtype, in, out, n, stream);
+    }
+    case 4: {
+      const void* const in[8] = {gy[0], dydx[0], gy[1], dydx[1], gy[2], dydx[2], gy[3], dydx[3]};
+      return run<BwdMultiOp<4>>(dtype, in, out, n, stream);
+    }
+  }
+  return NFAD_EINVAL_KIND;
 }
 
 int nfad_recompute_fwd(int kind, const void* x, void* y, size_t n, int dtype, void* stream) {

@@ -23,7 +23,8 @@ def test_header_declares_the_expected_entry_points():
         "nfad_fwd", "nfad_bwd", "nfad_recompute_fwd", "nfad_recompute_bwd", "nfad_saveall_num_saved",
         "nfad_saveall_fwd", "nfad_saveall_bwd", "nfad_status_string", "nfad_version",
         "nfad_chain_count", "nfad_chain_name", "nfad_chain_program", "nfad_chain_fwd",
-        "nfad_chain_compile", "nfad_chain_release", "nfad_chain_log"])
+        "nfad_chain_compile", "nfad_chain_release", "nfad_chain_log", "nfad_chain_compile_multi",
+        "nfad_chain_num_outputs", "nfad_chain_fwd_multi", "nfad_bwd_multi"])
 
 
 def test_library_exports_every_declared_symbol():
@@ -87,6 +88,19 @@ def test_malformed_chain_programs_are_rejected_on_the_host():
     assert L.nfad_chain_compile(None, ctypes.byref(cid)) == 3
     assert L.nfad_chain_compile(b"x tanh", None) == 3
     assert L.nfad_chain_release(5) == 1 and L.nfad_chain_release(1000 + 12345) == 1
+    progs = (ctypes.c_char_p * 5)(b"x tanh", b"x exp", b"x x *", b"x neg", b"x sigmoid")
+    assert L.nfad_chain_compile_multi(progs, 0, ctypes.byref(cid)) == 1
+    assert L.nfad_chain_compile_multi(progs, 5, ctypes.byref(cid)) == 1
+    bad = (ctypes.c_char_p * 2)(b"x tanh", b"x +")
+    assert L.nfad_chain_compile_multi(bad, 2, ctypes.byref(cid)) == 7 and "program 1" in nfad.nfad_chain_log()
+    assert nfad.nfad_chain_num_outputs(0) == 1 and nfad.nfad_chain_num_outputs(-3) == -1
+    A = 1 << 20
+    vpp = ctypes.c_void_p * 4
+    assert L.nfad_bwd_multi(vpp(A, A, A, A), vpp(A, A, A, A), 0, A, 4, 0, None) == 1
+    assert L.nfad_bwd_multi(vpp(A, A, A, A), vpp(A, A, A, A), 5, A, 4, 0, None) == 1
+    assert L.nfad_bwd_multi(vpp(A, None, A, A), vpp(A, A, A, A), 2, A, 4, 0, None) == 3
+    assert L.nfad_bwd_multi(None, None, 2, None, 0, 0, None) == 0
+    assert L.nfad_chain_fwd_multi(0, A, vpp(A, A, A, A), vpp(A, A, A, A), 4, 0, None) == 1    # built-in id
     assert nfad.nfad_chain_name(1000) is None or isinstance(nfad.nfad_chain_name(1000), str)
 
 

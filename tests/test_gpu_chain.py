@@ -128,3 +128,53 @@ def test_runtime_compiled_chains_match_interpreter(dtype):
             nfad.nfad_chain_fwd(cid, xd, y, d)
     with pytest.raises(nfad.NfadError):
         nfad.nfad_chain_release(ids[0])
+
+
+# ------------------------------------------------------------------ one source, several outputs
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("m", [2, 3, 4])
+def test_multi_output_chain_and_merged_backward(m, dtype):
+    td = DTYPES[dtype]
+    programs = ["x tanh x *", "x tanh sigmoid", "x x * neg exp", "x 0.5 * softplus"][:m]
+    cid = nfad.nfad_chain_compile_multi(programs)
+    assert nfad.nfad_chain_num_outputs(cid) == m and nfad.nfad_chain_program(cid) == " ; ".join(programs)
+    a = inputs.gaussian(N, 2.0, 7400 + m)
+    x = inputs.to_storage(np.clip(a, -9.0, 9.0), dtype)
+    x64 = inputs.storage_to_f64(x)
+    xd = x.to(DEV)
+    ys = [torch.full_like(xd, float("nan")) for _ in range(m)]
+    ds = [torch.full_like(xd, float("nan")) for _ in range(m)]
+    nfad.nfad_chain_fwd_multi(cid, xd, ys, ds)
+    rel = 2e-6 * np.maximum(1.0, np.abs(x64)) ** 2
+    refs = [chain.eval_chain(p, x64) for p in programs]
+    for j in range(m):
+        compare(ys[j], refs[j][0], td, f"multi y{j} {dtype}", extra_tol=rel * np.maximum(1.0, np.abs(refs[j][0])))
+        compare(ds[j], refs[j][1], td, f"multi d{j} {dtype}", extra_tol=rel * np.maximum(1.0, np.abs(refs[j][1])))
+    with pytest.raises(nfad.NfadError):
+        nfad.nfad_chain_fwd(cid, xd, ys[0], ds[0])             # a multi-output id needs the multi call
+    with pytest.raises(nfad.NfadError):
+        nfad.nfad_chain_fwd_multi(cid, xd, ys, [ds[0]] * m)    # coinciding outputs
+
+    # backward: tangents of all consumers merge at the source; inputs are the ORACLE's tangents, stored
+    gys = [inputs.to_storage(inputs.gaussian(N, 1.0, 7500 + 10 * m + j), dtype) for j in range(m)]
+    dst = [inputs.to_storage(refs[j][1].astype(np.float32), dtype) for j in range(m)]
+    gx_ref = sum(inputs.storage_to_f64(gys[j]) * inputs.storage_to_f64(dst[j]) for j in range(m))
+    gx = torch.full_like(xd, float("nan"))
+    nfad.nfad_bwd_multi([g.to(DEV) for g in gys], [d.to(DEV) for d in dst], gx)
+    mag = sum(np.abs(inputs.storage_to_f64(gys[j]) * inputs.storage_to_f64(dst[j])) for j in range(m))
+    compare(gx, gx_ref, td, f"bwd_multi m={m} {dtype}", extra_tol=4e-7 * mag)
+    nfad.nfad_chain_release(cid)
+
+
+def test_multi_output_autograd_front_end():
+    from paper_2209_10778_amd import autograd as A
+    programs = ["x tanh x *", "x tanh sigmoid"]
+    x = inputs.to_storage(np.clip(inputs.gaussian(30_000, 2.0, 7600), -9, 9), "f32")
+    x64 = inputs.storage_to_f64(x)
+    xd = x.to(DEV).requires_grad_(True)
+    a, b = A.chain_multi(xd, programs)
+    assert len(a.grad_fn.saved_tensors) == 2
+    (a.sum() + 2.0 * b.sum()).backward()
+    d1 = chain.eval_chain(programs[0], x64)[1]
+    d2 = chain.eval_chain(programs[1], x64)[1]
+    compare(xd.grad, d1 + 2.0 * d2, torch.float32, "multi autograd", extra_tol=1e-5 * np.maximum(1, np.abs(x64)))
