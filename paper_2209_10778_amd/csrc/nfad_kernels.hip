@@ -325,4 +325,8 @@ const char* nfad_status_string(int status) {
 
 int nfad_version(void) { return 100; }
 
+#ifdef NFAD_EXPERIMENT
+void nfad_experiment_set_waves(int waves) { nfad::g_waves_experiment = waves; }
+#endif
+
 }  // extern "C"

@@ -37,6 +37,10 @@ static DeviceInfo device_info() {
 
 // NFAD_WAVES_PER_CU (environment, read once): tuning aid that replaces the built-in cap on
 // resident waves per compute unit; 0 disables the cap.
+#ifdef NFAD_EXPERIMENT   /* experiment builds only: the override can be changed between launches */
+static int g_waves_experiment = -1;
+static int waves_per_cu_override() { return g_waves_experiment; }
+#else
 static int waves_per_cu_override() {
   static int cached = -2;
   int v = __atomic_load_n(&cached, __ATOMIC_RELAXED);
@@ -48,6 +52,7 @@ static int waves_per_cu_override() {
   }
   return v;
 }
+#endif
 
 // Dynamic-LDS bytes per block so that at most waves_per_cu waves are resident per CU.
 static unsigned lds_reservation(int waves_per_cu, int threads, int lds_per_cu) {
