@@ -2,7 +2,7 @@
 
 The paper deploys its method in PyTorch by overriding autograd Functions (Sec. V-A); this is
 the same hook for libnfad.  The forward pass runs the fused kernel (y and dydx in one pass
-over x), keeps only `dydx` for backward (Sec. II-C eq. 3, "only store ... v3'"), and the
+over x), keeps only `dydx` for backward (Sec. II-C eq. 3: the tangent v3' is the one stored value), and the
 backward pass is the single multiply gx = gy * dydx (eq. 4).  `x` is not saved, so its
 buffer is free as soon as no other operator holds it.
 
