@@ -20,12 +20,15 @@
  * Ownership : the caller owns every buffer.  The library never allocates, frees or
  *             keeps a pointer, and has no state (thread-safe, re-entrant).
  * Stream    : `stream` is a hipStream_t passed as void*; NULL is the default stream.
- *             Calls enqueue work and return; they never synchronise.
+ *             Calls enqueue work and return; they never synchronise, allocate or copy,
+ *             so they may be captured into a HIP graph.
  * Math      : fp32 internally for all dtypes; fp16/bf16 results are rounded once,
  *             to nearest even, on store.  Swish uses beta = 1 (Table I).
  * Alignment : pointers must be aligned to the element size (else NFAD_EALIGN).
  *             If every pointer of a call is 16-byte aligned the 128-bit vector body
- *             runs; otherwise a scalar kernel produces the same values.
+ *             runs.  If all are misaligned by the same amount (equal views of aligned
+ *             tensors) a few leading elements take a scalar kernel and the rest the
+ *             vector body; otherwise a scalar kernel produces the same values, slower.
  * Aliasing  : an output may coincide EXACTLY with an input of the same call
  *             (y == x, gx == gy, gx == dydx, gx == saved[j]); two outputs must not
  *             coincide (NFAD_EALIAS).  Partial overlap is undefined.

@@ -303,15 +303,20 @@ static int forward_m(const Compiled* c, const void* x, void* const* y, void* con
   for (int j = 0; j < M; ++j) { out[2 * j] = y[j]; out[2 * j + 1] = dydx[j]; }
   const int rc = validate<1, 2 * M>(in, out, n, dtype);
   if (rc != NFAD_OK || n == 0) return rc;
-  Ptrs<1, 2 * M> p;
+  using P = Ptrs<1, 2 * M>;
+  P p;
   p.in[0] = x;
   for (int o = 0; o < 2 * M; ++o) p.out[o] = out[o];
-  void* params[2] = {&p, &n};
-  const bool vec = all_aligned16(p);
-  const Geometry g = vec ? vec_geometry<1, 2 * M>(n, dtype == NFAD_F32 ? 4 : 8) : scalar_geometry(n);
-  const hipError_t e = hipModuleLaunchKernel(vec ? c->vec[dtype] : c->scalar[dtype], g.grid, 1, 1, g.threads, 1, 1,
-                                             g.lds, reinterpret_cast<hipStream_t>(stream), params, nullptr);
-  return e == hipSuccess ? NFAD_OK : NFAD_ELAUNCH;
+  hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+  auto enqueue = [s](hipFunction_t f, const P& q, size_t m, Geometry g) {
+    P args = q;
+    void* params[2] = {&args, &m};
+    return hipModuleLaunchKernel(f, g.grid, 1, 1, g.threads, 1, 1, g.lds, s, params, nullptr);
+  };
+  return launch_planned(
+      p, n, elem_size(dtype),
+      [&](const P& q, size_t m, Geometry g) { return enqueue(c->vec[dtype], q, m, g); },
+      [&](const P& q, size_t m, Geometry g) { return enqueue(c->scalar[dtype], q, m, g); });
 }
 
 static int forward(const Compiled* c, const void* x, void* const* y, void* const* dydx, size_t n, int dtype,

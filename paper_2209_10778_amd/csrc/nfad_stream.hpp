@@ -85,29 +85,69 @@ static Geometry scalar_geometry(size_t n) {
   if (grid > cap) grid = cap;
   return {(unsigned)grid, (unsigned)kScalarThreads, 0u};
 }
-// The 16-byte vector body needs every pointer of the call 16-byte aligned.
+// How a call is carried out.  The 16-byte vector kernel needs every pointer 16-byte aligned.
+// If all pointers are misaligned by the SAME amount (a view such as t[1:] of aligned tensors),
+// `head` leading elements go through the scalar kernel and the rest, now aligned, through the
+// vector kernel; pointers with different misalignments take the scalar kernel throughout.
+struct Plan {
+  bool vec;
+  size_t head;
+};
 template <int NIN, int NOUT>
-static bool all_aligned16(const Ptrs<NIN, NOUT>& p) {
-  uintptr_t bits = 0;
-  for (int i = 0; i < NIN; ++i) bits |= (uintptr_t)p.in[i];
-  for (int o = 0; o < NOUT; ++o) bits |= (uintptr_t)p.out[o];
-  return (bits & 15u) == 0;
+static Plan make_plan(const Ptrs<NIN, NOUT>& p, size_t n, size_t elem_bytes) {
+  const uintptr_t mis = (uintptr_t)p.out[0] & 15u;
+  for (int i = 0; i < NIN; ++i)
+    if (((uintptr_t)p.in[i] & 15u) != mis) return {false, 0};
+  for (int o = 0; o < NOUT; ++o)
+    if (((uintptr_t)p.out[o] & 15u) != mis) return {false, 0};
+  if (mis == 0) return {true, 0};
+  const size_t head = (16 - mis) / elem_bytes;   // pointers are element-aligned, so this is exact
+  if (n <= head) return {false, 0};
+  return {true, head};
+}
+template <int NIN, int NOUT>
+static Ptrs<NIN, NOUT> advanced(const Ptrs<NIN, NOUT>& p, size_t bytes) {
+  Ptrs<NIN, NOUT> q;
+  for (int i = 0; i < NIN; ++i) q.in[i] = static_cast<const char*>(p.in[i]) + bytes;
+  for (int o = 0; o < NOUT; ++o) q.out[o] = static_cast<char*>(p.out[o]) + bytes;
+  return q;
+}
+// Runs a call according to its plan.  launch_vec(ptrs, n, geometry) and launch_scalar(ptrs, n,
+// geometry) enqueue the two kernels and return a hipError_t.
+template <int NIN, int NOUT, class LaunchVec, class LaunchScalar>
+static int launch_planned(const Ptrs<NIN, NOUT>& p, size_t n, size_t elem_bytes, LaunchVec launch_vec,
+                          LaunchScalar launch_scalar) {
+  const Plan plan = make_plan(p, n, elem_bytes);
+  hipError_t e = hipSuccess;
+  if (!plan.vec) {
+    e = launch_scalar(p, n, scalar_geometry(n));
+  } else {
+    if (plan.head) e = launch_scalar(p, plan.head, scalar_geometry(plan.head));
+    if (e == hipSuccess) {
+      const size_t rest = n - plan.head;
+      e = launch_vec(advanced(p, plan.head * elem_bytes), rest, vec_geometry<NIN, NOUT>(rest, (int)(16 / elem_bytes)));
+    }
+  }
+  return e == hipSuccess ? NFAD_OK : NFAD_ELAUNCH;
 }
 
 template <class Op, typename T>
 static int launch(const void* const (&in)[Op::kIn], void* const (&out)[Op::kOut], size_t n,
                   hipStream_t stream) {
-  Ptrs<Op::kIn, Op::kOut> p;
+  using P = Ptrs<Op::kIn, Op::kOut>;
+  P p;
   for (int i = 0; i < Op::kIn; ++i) p.in[i] = in[i];
   for (int o = 0; o < Op::kOut; ++o) p.out[o] = out[o];
-  if (all_aligned16(p)) {
-    const Geometry g = vec_geometry<Op::kIn, Op::kOut>(n, Storage<T>::kVec);
-    hipLaunchKernelGGL((ew_vec_kernel<Op, T>), dim3(g.grid), dim3(g.threads), g.lds, stream, p, n);
-  } else {
-    const Geometry g = scalar_geometry(n);
-    hipLaunchKernelGGL((ew_scalar_kernel<Op, T>), dim3(g.grid), dim3(g.threads), 0, stream, p, n);
-  }
-  return hipGetLastError() == hipSuccess ? NFAD_OK : NFAD_ELAUNCH;
+  return launch_planned(
+      p, n, sizeof(T),
+      [stream](const P& q, size_t m, Geometry g) {
+        hipLaunchKernelGGL((ew_vec_kernel<Op, T>), dim3(g.grid), dim3(g.threads), g.lds, stream, q, m);
+        return hipGetLastError();
+      },
+      [stream](const P& q, size_t m, Geometry g) {
+        hipLaunchKernelGGL((ew_scalar_kernel<Op, T>), dim3(g.grid), dim3(g.threads), 0, stream, q, m);
+        return hipGetLastError();
+      });
 }
 
 template <class Op>

@@ -131,3 +131,38 @@ def test_product_path_does_not_import_the_oracle():
                 assert "nfad_oracle" not in text, f
     otext = open(os.path.join(ROOT, "oracle", "__init__.py")).read() + open(os.path.join(ROOT, "oracle", "nfad_oracle.c")).read()
     assert "paper_2209_10778_amd" not in otext
+
+
+def test_header_is_plain_c_and_links(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 with warnings as errors, and a C
+    program must link against the library and reach the host-side validation."""
+    import subprocess
+    src = tmp_path / "abi.c"
+    src.write_text(r"""
+#include "nfad.h"
+#include <stdio.h>
+int main(void) {
+  float buf[64];   /* 256 bytes; host memory: validation never dereferences it */
+  void* a = (void*)(((size_t)buf + 63) & ~(size_t)63);
+  void* b = (char*)a + 64;
+  void* c = (char*)a + 128;
+  int ok = 1;
+  ok &= nfad_fwd(99, a, b, c, 4, NFAD_F32, 0) == NFAD_EINVAL_KIND;
+  ok &= nfad_fwd(NFAD_MISH, a, b, b, 4, NFAD_F32, 0) == NFAD_EALIAS;
+  ok &= nfad_bwd(a, 0, c, 4, NFAD_BF16, 0) == NFAD_ENULL;
+  ok &= nfad_fwd(NFAD_SWISH, 0, 0, 0, 0, NFAD_F16, 0) == NFAD_OK;
+  ok &= nfad_saveall_num_saved(NFAD_GELU_TANH) == NFAD_MAX_SAVED;
+  ok &= nfad_chain_count() > 0 && nfad_chain_name(0) != 0 && nfad_chain_program(0) != 0;
+  ok &= nfad_version() >= 100;
+  printf("%s\n", nfad_status_string(NFAD_EALIGN));
+  return ok ? 0 : 1;
+}
+""")
+    exe = tmp_path / "abi"
+    libdir = os.path.dirname(nfad.lib_path())
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe), "-L", libdir, "-lnfad", f"-Wl,-rpath,{libdir}",
+                    "-Wl,-rpath,/opt/rocm/lib"], check=True)
+    r = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "aligned" in r.stdout

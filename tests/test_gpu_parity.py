@@ -249,6 +249,98 @@ def test_misaligned_pointers_take_the_scalar_kernel(dtype):
             assert bool((bd[:off_d] == 777.0).all()) and bool((bd[off_d + n:] == 777.0).all())
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_equally_misaligned_views_peel_a_head_and_stay_exact(dtype):
+    """x[k:], y[k:], d[k:] of aligned tensors: a scalar head, then the vector body.  The result
+    must be bit-identical to the aligned call and nothing outside the views may be written."""
+    td = DTYPES[dtype]
+    n = N_RAGGED
+    for kind in (nfad.GELU_TANH, nfad.MISH):
+        x = stress_x(n + 16, 7500 + kind, dtype)
+        xd = dev(x)
+        for k in (1, 2, 3, 5, 7):
+            m = n + 16 - k - 3
+            y_al, d_al = torch.empty(m, dtype=td, device=DEV), torch.empty(m, dtype=td, device=DEV)
+            nfad.nfad_fwd(kind, xd[k:k + m].clone(), y_al, d_al)             # aligned reference run
+            by = torch.full((n + 16,), 777.0, dtype=td, device=DEV)
+            bd = torch.full((n + 16,), 777.0, dtype=td, device=DEV)
+            nfad.nfad_fwd(kind, xd[k:k + m], by[k:k + m], bd[k:k + m])
+            assert torch.equal(by[k:k + m], y_al) and torch.equal(bd[k:k + m], d_al), (kind, k)
+            for b in (by, bd):
+                assert bool((b[:k] == 777.0).all()) and bool((b[k + m:] == 777.0).all()), (kind, k)
+        y_ref, d_ref = oracle.fwd(kind, inputs.storage_to_f64(x[1:1 + n]))
+        y, d = torch.empty(n + 1, dtype=td, device=DEV), torch.empty(n + 1, dtype=td, device=DEV)
+        nfad.nfad_fwd(kind, xd[1:1 + n], y[1:], d[1:])
+        compare(y[1:], y_ref, td, "peeled y")
+        compare(d[1:], d_ref, td, "peeled d")
+
+
+def test_capture_in_a_hip_graph_and_replay():
+    """Callers that capture the calls in a HIP graph: every replay must match the oracle on the
+    data that is in the static buffers at that moment (eager work in between)."""
+    kind, dtype, td = nfad.GELU_ERF, "bf16", torch.bfloat16
+    n = N_RAGGED
+    x_static = torch.zeros(n, dtype=td, device=DEV)
+    gy_static = torch.zeros(n, dtype=td, device=DEV)
+    y, d, gx = (torch.empty(n, dtype=td, device=DEV) for _ in range(3))
+    nfad.nfad_fwd(kind, x_static, y, d)        # warm the per-device caches outside the capture
+    nfad.nfad_bwd(gy_static, d, gx)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        nfad.nfad_fwd(kind, x_static, y, d)    # the binding picks up the capturing stream
+        nfad.nfad_bwd(gy_static, d, gx)
+    for rep in range(4):
+        x = stress_x(n, 9600 + rep, dtype)
+        gy = inputs.to_storage(inputs.gaussian(n, 0.3, 9700 + rep), dtype)
+        x_static.copy_(dev(x))
+        gy_static.copy_(dev(gy))
+        y.fill_(float("nan")); d.fill_(float("nan")); gx.fill_(float("nan"))
+        g.replay()
+        torch.cuda.synchronize()
+        x64, gy64 = inputs.storage_to_f64(x), inputs.storage_to_f64(gy)
+        y_ref, d_ref = oracle.fwd(kind, x64)
+        compare(y, y_ref, td, f"graph replay {rep} y")
+        compare(d, d_ref, td, f"graph replay {rep} d")
+        # gx is the exact product of the stored tangent the graph itself wrote (bit-level check in fp64)
+        gx_expect = (gy_static.double() * d.double()).to(td)
+        assert torch.equal(gx, gx_expect), f"graph replay {rep} gx"
+        _ = (y.float() * 2).sum().item()       # eager work between replays
+
+
+def test_concurrent_host_threads_on_their_own_streams():
+    import threading
+    kind, dtype, td = nfad.SWISH, "f32", torch.float32
+    n = 200_003
+    results, errors = {}, []
+
+    def worker(tid):
+        try:
+            torch.cuda.set_device(0)
+            s = torch.cuda.Stream()
+            x = stress_x(n, 9800 + tid, dtype)
+            xd = dev(x)
+            y, d = torch.empty_like(xd), torch.empty_like(xd)
+            torch.cuda.synchronize()
+            for _ in range(20):
+                nfad.nfad_fwd(kind, xd, y, d, stream=s)
+            s.synchronize()
+            results[tid] = (x, y, d)
+        except Exception as e:  # noqa: BLE001
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(t,)) for t in range(6)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    for tid, (x, y, d) in results.items():
+        y_ref, d_ref = oracle.fwd(kind, inputs.storage_to_f64(x))
+        compare(y, y_ref, td, f"thread {tid} y")
+        compare(d, d_ref, td, f"thread {tid} d")
+
+
 def test_exact_aliasing_is_allowed():
     td = torch.float32
     n = N_RAGGED
