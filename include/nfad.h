@@ -107,8 +107,9 @@ int nfad_saveall_bwd(int kind, const void* gy, const void* const* saved, void* g
                      int dtype, void* stream);
 
 /* Composed chains (Sec. III-A: any composition of "fad" primitive operations that maps one
- * source element to one result; primitives: + - * / neg exp log tanh sigmoid softplus erf,
- * constants, and the source x).  The library carries a table of chains built from those
+ * source element to one result; primitives: + - * / min max neg exp log tanh sigmoid
+ * softplus erf relu abs sqrt, constants, and the source x; at a kink the tangent of relu and
+ * abs is 0 and min/max follow their first operand).  The library carries a table of chains built from those
  * primitives with a compile-time dual-number composer; each is fused into ONE forward
  * kernel with the contract of nfad_fwd: y[i] = f(x[i]), dydx[i] = f'(x[i]), f' obtained by
  * pushing the dual number (x, 1) through the primitives (Sec. II-C eq. 3, Sec. II-D).
@@ -127,7 +128,7 @@ int nfad_chain_fwd(int chain_id, const void* x, void* y, void* dydx, size_t n, i
 /* Run-time composed chains: the counterpart of the paper's automatic graph rewrite
  * (Sec. III-B, Sec. IV), which finds a chain of fad operations and replaces its forward and
  * backward passes.  `program` is ANY chain in the postfix notation above (tokens separated
- * by blanks: x, decimal constants, + - * / neg exp log tanh sigmoid softplus erf; at most
+ * by blanks: x, decimal constants and the primitive names listed above; at most
  * 256 tokens; must use x and leave exactly one value).  The library compiles one fused
  * forward kernel for it on the current device (hiprtc; about a second) and returns a chain
  * id >= NFAD_CHAIN_JIT_BASE in *chain_id, valid for nfad_chain_fwd / _name / _program on

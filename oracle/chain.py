@@ -3,9 +3,10 @@
 TEST INFRASTRUCTURE ONLY (same rules as the rest of this package).
 
 A chain is a postfix program over the paper's primitive operations (Sec. III-A, Sec. V-A):
-tokens are `x` (the source element), decimal constants, the binary operators `+ - * /`
+tokens are `x` (the source element), decimal constants, the binary operators `+ - * / min max`
 (both operands derive from the same source, or one is a constant) and the unary primitives
-`neg exp log tanh sigmoid softplus erf`.  Every stack entry is a pair (v, v') of float64
+`neg exp log tanh sigmoid softplus erf relu abs sqrt`.  At a kink the tangent of relu and abs is
+0 and min/max follow their first operand.  Every stack entry is a pair (v, v') of float64
 arrays; `x` pushes (x, 1) and each primitive applies its textbook derivative rule
 (Sec. II-D: v' = sum over inputs of dv/du * u').  The result is (y, dydx).
 
@@ -30,6 +31,9 @@ _UNARY = {
     "sigmoid": lambda v, d: (_sigmoid(v), _sigmoid(v) * _sigmoid(-v) * d),
     "softplus": lambda v, d: (np.logaddexp(0.0, v), _sigmoid(v) * d),
     "erf": lambda v, d: (_sp.erf(v), 2.0 / np.sqrt(np.pi) * np.exp(-v * v) * d),
+    "relu": lambda v, d: (np.maximum(v, 0.0), np.where(v > 0.0, d, 0.0)),
+    "abs": lambda v, d: (np.abs(v), np.sign(v) * d),
+    "sqrt": lambda v, d: (np.sqrt(v), d / (2.0 * np.sqrt(v))),
 }
 
 _BINARY = {
@@ -37,6 +41,8 @@ _BINARY = {
     "-": lambda a, da, b, db: (a - b, da - db),
     "*": lambda a, da, b, db: (a * b, a * db + da * b),
     "/": lambda a, da, b, db: (a / b, (da - (a / b) * db) / b),
+    "min": lambda a, da, b, db: (np.where(a <= b, a, b), np.where(a <= b, da, db)),
+    "max": lambda a, da, b, db: (np.where(a >= b, a, b), np.where(a >= b, da, db)),
 }
 
 

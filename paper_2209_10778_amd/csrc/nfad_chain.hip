@@ -30,6 +30,12 @@ using GeluErfC = Mul<Mul<Const<kHalf>, X>, Add<Const<kOne>, Erf<Mul<Const<kInvSq
 using TanhShrinkC = Sub<X, Tanh<X>>;                                         // x - tanh x
 using LogSigmoidC = Neg<Softplus<Neg<X>>>;                                   // -softplus(-x)
 using SwishSigmoidC = Mul<Sigmoid<X>, X>;                                    // v1 = sigmoid(x), v2 = x, v3 = v1 v2
+NFAD_CHAIN_CONSTANT(kZero, 0.0f);
+NFAD_CHAIN_CONSTANT(kThree, 3.0f);
+NFAD_CHAIN_CONSTANT(kSix, 6.0f);
+using EluC = Add<Relu<X>, Sub<Exp<Min<X, Const<kZero>>>, Const<kOne>>>;      // relu(x) + exp(min(x,0)) - 1
+using HardSwishC = Div<Mul<X, Min<Max<Add<X, Const<kThree>>, Const<kZero>>, Const<kSix>>>, Const<kSix>>;
+using SoftsignC = Div<X, Add<Const<kOne>, Abs<X>>>;                          // x / (1 + |x|)
 }  // namespace chain
 
 struct ChainEntry {
@@ -48,6 +54,9 @@ static const ChainEntry kChains[] = {
     {"tanhshrink", "x x tanh -"},
     {"logsigmoid", "x neg softplus neg"},
     {"swish_sigmoid", "x sigmoid x *"},
+    {"elu", "x relu x 0 min exp 1 - +"},
+    {"hardswish", "x x 3 + 0 max 6 min * 6 /"},
+    {"softsign", "x 1 x abs + /"},
 };
 static constexpr int kNumChains = (int)(sizeof(kChains) / sizeof(kChains[0]));
 
@@ -110,6 +119,9 @@ int nfad_chain_fwd(int chain_id, const void* x, void* y, void* dydx, size_t n, i
     case 8: return run<ChainFwdOp<chain::TanhShrinkC>>(dtype, in, out, n, stream);
     case 9: return run<ChainFwdOp<chain::LogSigmoidC>>(dtype, in, out, n, stream);
     case 10: return run<ChainFwdOp<chain::SwishSigmoidC>>(dtype, in, out, n, stream);
+    case 11: return run<ChainFwdOp<chain::EluC>>(dtype, in, out, n, stream);
+    case 12: return run<ChainFwdOp<chain::HardSwishC>>(dtype, in, out, n, stream);
+    case 13: return run<ChainFwdOp<chain::SoftsignC>>(dtype, in, out, n, stream);
   }
   return NFAD_EINVAL_KIND;
 }
@@ -156,7 +168,8 @@ static thread_local std::string g_log;
 // postfix program -> C++ type expression over nfad::chain templates (+ constant definitions)
 static bool translate(const char* program, int index, std::string& consts, std::string& type, std::string& err) {
   static const struct { const char* tok; const char* tmpl; int arity; } kOps[] = {
-      {"+", "Add", 2}, {"-", "Sub", 2}, {"*", "Mul", 2}, {"/", "Div", 2}, {"neg", "Neg", 1},
+      {"+", "Add", 2}, {"-", "Sub", 2}, {"*", "Mul", 2}, {"/", "Div", 2}, {"min", "Min", 2}, {"max", "Max", 2},
+      {"neg", "Neg", 1}, {"relu", "Relu", 1}, {"abs", "Abs", 1}, {"sqrt", "Sqrt", 1},
       {"exp", "Exp", 1}, {"log", "Log", 1}, {"tanh", "Tanh", 1}, {"sigmoid", "Sigmoid", 1},
       {"softplus", "Softplus", 1}, {"erf", "Erf", 1}};
   std::vector<std::string> stack;

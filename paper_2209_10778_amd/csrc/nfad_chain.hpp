@@ -3,7 +3,9 @@
 // The paper's method applies to any composition of "fad" primitive operations that maps one
 // source element to one result (Sec. III-A: unary operations, binary operations with a
 // constant, binary operations whose two inputs come from the same source; the symbolic
-// primitives tanh, sigmoid, softplus; Sec. V-A lists add, mul, exp, tanh, softplus, sigmoid).
+// primitives tanh, sigmoid, softplus; Sec. V-A lists add, mul, exp, tanh, softplus, sigmoid
+// "etc."; the piecewise primitives relu, abs, min, max and sqrt are added here so that ELU,
+// hard-swish, softsign and the like are chains too).
 // Here such a chain is a TYPE built from the templates below; evaluating it pushes the dual
 // number (x, 1) through the primitives (Sec. II-C eq. 3, Sec. II-D: v' = sum dv/du * u'), all
 // in registers, and the result (value, tangent) is (y, dydx) of the fused forward kernel.
@@ -81,7 +83,45 @@ struct Div {  // (a/b)' = (a' - (a/b) b') / b
   }
 };
 
+template <class A, class B>
+struct Min {  // the tangent follows the selected operand (the first on a tie)
+  __device__ __forceinline__ static Dual eval(Dual x) {
+    const Dual a = A::eval(x), b = B::eval(x);
+    return a.v <= b.v ? a : (b.v < a.v ? b : Dual{a.v + b.v, a.d + b.d});  // last arm: a NaN stays NaN
+  }
+};
+template <class A, class B>
+struct Max {
+  __device__ __forceinline__ static Dual eval(Dual x) {
+    const Dual a = A::eval(x), b = B::eval(x);
+    return a.v >= b.v ? a : (b.v > a.v ? b : Dual{a.v + b.v, a.d + b.d});
+  }
+};
+
 // ---------------------------------------------------------------- unary
+template <class A>
+struct Relu {  // max(v, 0); tangent 0 at and below the kink
+  __device__ __forceinline__ static Dual eval(Dual x) {
+    const Dual a = A::eval(x);
+    return a.v > 0.0f ? a : Dual{a.v * 0.0f, a.d * 0.0f};  // v * 0 keeps NaN, gives -0 for v < 0
+  }
+};
+template <class A>
+struct Abs {  // tangent sign(v) v', 0 at the kink
+  __device__ __forceinline__ static Dual eval(Dual x) {
+    const Dual a = A::eval(x);
+    const float sgn = a.v > 0.0f ? 1.0f : (a.v < 0.0f ? -1.0f : a.v * 0.0f);
+    return Dual{__builtin_fabsf(a.v), sgn * a.d};
+  }
+};
+template <class A>
+struct Sqrt {  // (sqrt v)' = v' / (2 sqrt v)
+  __device__ __forceinline__ static Dual eval(Dual x) {
+    const Dual a = A::eval(x);
+    const float r = __builtin_amdgcn_sqrtf(a.v);
+    return Dual{r, (0.5f * a.d) * rcp(r)};
+  }
+};
 template <class A>
 struct Neg {
   __device__ __forceinline__ static Dual eval(Dual x) {

@@ -104,8 +104,11 @@ def _bin(tok):
 
 _UNARY = {
     "neg": _un("neg"), "exp": _un("exp"), "log": _un("log"), "tanh": _un("tanh"), "sigmoid": _un("sigmoid"),
-    "softplus": _un("softplus"), "erf": _un("erf"),
+    "softplus": _un("softplus"), "erf": _un("erf"), "relu": _un("relu"), "abs": _un("abs"), "sqrt": _un("sqrt"),
     "square": lambda a: a + a + ["*"],
+    "relu6": lambda a: a + ["0", "max", "6", "min"],
+    "hardswish": lambda a: a + a + ["3", "+", "0", "max", "6", "min", "*", "6", "/"],
+    "softsign": lambda a: a + ["1"] + a + ["abs", "+", "/"],
     "silu": lambda a: a + a + ["sigmoid", "*"],
     "mish": lambda a: a + a + ["softplus", "tanh", "*"],
     "gelu_erf": lambda a: ["0.5"] + a + ["*", "1", repr(1.0 / math.sqrt(2.0))] + a + ["*", "erf", "+", "*"],
@@ -123,7 +126,9 @@ def _op_name(func):
         "div": "div", "true_divide": "div", "__truediv__": "div", "__rtruediv__": "rdiv", "__rdiv__": "rdiv", "__div__": "div", "divide": "div",
         "neg": "neg", "negative": "neg", "__neg__": "neg", "exp": "exp", "log": "log", "tanh": "tanh",
         "sigmoid": "sigmoid", "softplus": "softplus", "erf": "erf", "square": "square", "silu": "silu",
-        "mish": "mish", "gelu": "gelu", "pow": "pow", "__pow__": "pow",
+        "mish": "mish", "gelu": "gelu", "pow": "pow", "__pow__": "pow", "relu": "relu", "abs": "abs",
+        "absolute": "abs", "__abs__": "abs", "sqrt": "sqrt", "relu6": "relu6", "hardswish": "hardswish",
+        "softsign": "softsign", "elu": "elu", "clamp": "clamp", "clip": "clamp",
     }
     return table.get(n)
 
@@ -173,6 +178,25 @@ class fuse(TorchFunctionMode):
             if len(args) == 1 and kwargs.get("beta", 1.0) == 1.0 and kwargs.get("threshold", 20.0) == 20.0:
                 a = self._operand(args[0], source)
                 prog = None if a is None else _UNARY["softplus"](a)
+        elif op == "elu":
+            alpha = kwargs.get("alpha", 1.0)
+            if len(args) == 1 and set(kwargs) <= {"alpha", "inplace"} and not kwargs.get("inplace", False) \
+                    and _const(alpha) is not None:
+                a = self._operand(args[0], source)
+                if a is not None:       # relu(a) + alpha * (exp(min(a, 0)) - 1)
+                    prog = a + ["relu", _const(alpha)] + a + ["0", "min", "exp", "1", "-", "*", "+"]
+        elif op == "clamp":
+            lo = args[1] if len(args) > 1 else kwargs.get("min")
+            hi = args[2] if len(args) > 2 else kwargs.get("max")
+            if set(kwargs) <= {"min", "max"} and len(args) <= 3 and (lo is not None or hi is not None) \
+                    and all(v is None or _const(v) is not None for v in (lo, hi)):
+                a = self._operand(args[0], source)
+                if a is not None:
+                    prog = list(a)
+                    if lo is not None:
+                        prog += [_const(lo), "max"]
+                    if hi is not None:
+                        prog += [_const(hi), "min"]
         elif op == "pow":
             if len(args) == 2 and not kwargs and isinstance(args[1], int) and not isinstance(args[1], bool) \
                     and 2 <= args[1] <= 8:

@@ -25,7 +25,11 @@ MP = {
     "gelu_erf": lambda x: mp.mpf("0.5") * x * (1 + mp.erf(x / mp.sqrt(2))),
     "tanhshrink": lambda x: x - mp.tanh(x),
     "logsigmoid": lambda x: -mp.log(1 + mp.exp(-x)),
+    "elu": lambda x: x if x > 0 else mp.exp(x) - 1,
+    "hardswish": lambda x: x * min(max(x + 3, 0), 6) / 6,
+    "softsign": lambda x: x / (1 + abs(x)),
 }
+KINKS = {"elu": (0.0,), "hardswish": (-3.0, 3.0), "softsign": (0.0,)}
 SAME_AS_KIND = {"swish_table1": oracle.SWISH, "swish_sigmoid": oracle.SWISH, "mish_table1": oracle.MISH,
                 "gelu_tanh_table1": oracle.GELU_TANH, "gelu_erf": oracle.GELU_ERF}
 
@@ -43,6 +47,7 @@ def test_every_library_chain_has_an_independent_spelling():
 @pytest.mark.parametrize("cid,name,program", library_chains())
 def test_interpreter_matches_mpmath(cid, name, program):
     xs = np.array([-9.5, -4.0, -1.7, -0.6, -0.01, 0.0, 0.02, 0.5, 1.3, 3.0, 7.25])
+    xs = np.array([v for v in xs if v not in KINKS.get(name, ())])     # no derivative at a kink
     y, d = chain.eval_chain(program, xs)
     f = MP[name]
     for i, xv in enumerate(xs):
@@ -72,6 +77,17 @@ def test_product_rule_and_quotient_rule_by_hand():
     assert np.allclose(d, 2 * np.exp(2 * x), rtol=1e-15)
     y, d = chain.eval_chain("x log", np.array([0.25, 2.0]))
     assert np.allclose(d, [4.0, 0.5])
+
+
+def test_piecewise_primitives_at_their_kinks():
+    x = np.array([-2.0, 0.0, 3.0])
+    assert chain.eval_chain("x relu", x)[1].tolist() == [0.0, 0.0, 1.0]
+    assert chain.eval_chain("x abs", x)[1].tolist() == [-1.0, 0.0, 1.0]
+    assert chain.eval_chain("x 0 max", x)[1].tolist() == [0.0, 1.0, 1.0]       # first operand on a tie
+    assert chain.eval_chain("0 x max", x)[1].tolist() == [0.0, 0.0, 1.0]
+    assert chain.eval_chain("x 3 min", x)[1].tolist() == [1.0, 1.0, 1.0]
+    v, d = chain.eval_chain("x x * sqrt", np.array([-2.0, 3.0]))                 # |x|
+    assert np.allclose(v, [2.0, 3.0]) and np.allclose(d, [-1.0, 1.0])
 
 
 def test_malformed_programs_are_rejected():

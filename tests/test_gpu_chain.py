@@ -92,6 +92,9 @@ JIT_PROGRAMS = [
     "x 1.702 x * sigmoid *",                    # the sigmoid approximation of GELU
     "x erf x * 0.25 x * -",                     # x erf(x) - x/4
     "1 x x * 1 + /",                            # 1/(1+x^2)
+    "x relu 1.5 x 0 min exp 1 - * +",           # ELU with alpha = 1.5
+    "x abs 1 + sqrt x *",                       # x sqrt(1 + |x|)
+    "x -1 max 2.5 min x *",                     # x clamp(x, -1, 2.5)
 ]
 
 

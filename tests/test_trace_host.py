@@ -55,6 +55,24 @@ def test_builtin_functionals_expand_to_primitives():
                      "rsub": "1.0 x -", "rdiv": "2.0 x /", "neg": "x neg", "sigmoid_method": "x sigmoid"}
 
 
+def test_piecewise_functionals_expand_to_primitives():
+    x = torch.randn(8)
+    with trace.fuse(require_cuda=False):
+        progs = {
+            "relu": " ".join(F.relu(x)._program),
+            "abs": " ".join(x.abs()._program),
+            "elu": " ".join(F.elu(x, alpha=0.5)._program),
+            "hardswish": " ".join(F.hardswish(x)._program),
+            "softsign": " ".join(F.softsign(x)._program),
+            "clamp": " ".join(torch.clamp(x, -1, 2.5)._program),
+            "clamp_kw": " ".join(x.clamp(min=0.0)._program),
+            "relu6": " ".join(F.relu6(x)._program),
+        }
+    assert progs == {"relu": "x relu", "abs": "x abs", "elu": "x relu 0.5 x 0 min exp 1 - * +",
+                     "hardswish": "x x 3 + 0 max 6 min * 6 /", "softsign": "x 1 x abs + /",
+                     "clamp": "x -1.0 max 2.5 min", "clamp_kw": "x 0.0 max", "relu6": "x 0 max 6 min"}
+
+
 def test_binary_operator_needs_the_same_source():
     x, w = torch.randn(4, 4), torch.randn(4, 4)
     with trace.fuse(require_cuda=False) as t:
@@ -69,9 +87,9 @@ def test_binary_operator_needs_the_same_source():
 def test_non_fad_operator_is_passed_through_untouched():
     x = torch.randn(3, 3)
     with trace.fuse(require_cuda=False) as t:
-        y = torch.relu(x) @ x             # neither is a fad primitive
+        y = torch.cumsum(x, 0) @ x        # neither is a fad primitive
     assert not isinstance(y, trace.Lazy) and active(t.states) == []
-    assert torch.equal(y, torch.relu(x) @ x)
+    assert torch.equal(y, torch.cumsum(x, 0) @ x)
 
 
 def test_unsupported_variants_do_not_start_a_chain():
