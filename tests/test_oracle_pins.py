@@ -199,6 +199,26 @@ def test_minimum_where_derivative_vanishes(kind):
     assert oracle.fwd(kind, [xs - 0.1])[0][0] > ymin < oracle.fwd(kind, [xs + 0.1])[0][0]
 
 
+@pytest.mark.parametrize("kind", oracle.KINDS)
+def test_extrema_of_the_derivative(kind):
+    """The derivative overshoots 1 on the right and dips below 0 on the left; location and height of
+    both extrema against the 150-digit definition (root of the second derivative)."""
+    f = _def(kind)
+    dfun = lambda v: oracle.fwd(kind, [v])[1][0]
+    hi = scipy.optimize.minimize_scalar(lambda v: -dfun(v), bounds=(0.5, 4.0), method="bounded",
+                                        options={"xatol": 1e-10})
+    lo = scipy.optimize.minimize_scalar(dfun, bounds=(-4.0, -0.5), method="bounded", options={"xatol": 1e-10})
+    x_hi = mp.findroot(lambda v: mp.diff(f, v, 2), mp.mpf(hi.x))
+    x_lo = mp.findroot(lambda v: mp.diff(f, v, 2), mp.mpf(lo.x))
+    assert abs(hi.x - float(x_hi)) < 1e-5 and abs(lo.x - float(x_lo)) < 1e-5
+    assert abs(dfun(float(x_hi)) - float(mp.diff(f, x_hi))) < 1e-14
+    assert abs(dfun(float(x_lo)) - float(mp.diff(f, x_lo))) < 1e-14
+    assert 1.08 < dfun(float(x_hi)) < 1.13 and -0.13 < dfun(float(x_lo)) < -0.09
+    if kind in SYMMETRIC:       # f'(x) + f'(-x) = 1: the dip mirrors the overshoot
+        assert abs(float(x_hi) + float(x_lo)) < 1e-12
+        assert abs(dfun(float(x_hi)) + dfun(float(x_lo)) - 1.0) < 1e-14
+
+
 def test_bwd_is_plain_product():
     rng = np.random.default_rng(11)
     gy, dd = rng.normal(size=1000), rng.normal(size=1000)
