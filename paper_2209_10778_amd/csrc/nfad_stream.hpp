@@ -73,7 +73,7 @@ static Geometry vec_geometry(size_t n, int elems_per_vec) {
   const size_t nvec = n / (size_t)elems_per_vec;
   size_t grid = nvec / ((size_t)Shape::kThreads * Shape::kUnroll);   // one block per full tile
   if (grid == 0) grid = 1;
-  if (grid > (1u << 30)) grid = 1u << 30;
+  if (grid > (1u << 24)) grid = 1u << 24;   // grid x block stays below 2^32 threads; the kernel strides beyond
   int waves = waves_per_cu_override();
   if (waves < 0) waves = Shape::kWavesPerCu;
   return {(unsigned)grid, (unsigned)Shape::kThreads,
