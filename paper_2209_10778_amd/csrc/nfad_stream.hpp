@@ -54,6 +54,24 @@ static int waves_per_cu_override() {
 }
 #endif
 
+// Largest grid of the vector kernel.  One block per tile up to this many blocks; beyond it the
+// kernel's grid stride takes over.  2^24 blocks keeps grid x block below 2^32 threads.
+// NFAD_MAX_GRID (environment, read once) lowers it, which is how the striding path is tested.
+static size_t max_grid() {
+  static size_t cached = 0;
+  size_t v = __atomic_load_n(&cached, __ATOMIC_RELAXED);
+  if (v == 0) {
+    v = (size_t)1 << 24;
+    const char* s = getenv("NFAD_MAX_GRID");
+    if (s) {
+      const long long w = atoll(s);
+      if (w >= 1 && w < (long long)v) v = (size_t)w;
+    }
+    __atomic_store_n(&cached, v, __ATOMIC_RELAXED);
+  }
+  return v;
+}
+
 // Dynamic-LDS bytes per block so that at most waves_per_cu waves are resident per CU.
 static unsigned lds_reservation(int waves_per_cu, int threads, int lds_per_cu) {
   const int waves_per_block = threads / 64;
@@ -73,7 +91,7 @@ static Geometry vec_geometry(size_t n, int elems_per_vec) {
   const size_t nvec = n / (size_t)elems_per_vec;
   size_t grid = nvec / ((size_t)Shape::kThreads * Shape::kUnroll);   // one block per full tile
   if (grid == 0) grid = 1;
-  if (grid > (1u << 24)) grid = 1u << 24;   // grid x block stays below 2^32 threads; the kernel strides beyond
+  if (grid > max_grid()) grid = max_grid();
   int waves = waves_per_cu_override();
   if (waves < 0) waves = Shape::kWavesPerCu;
   return {(unsigned)grid, (unsigned)Shape::kThreads,

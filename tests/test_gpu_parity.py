@@ -409,6 +409,41 @@ def test_non_default_stream():
     compare(d, d_ref, td, "stream d")
 
 
+def test_grid_stride_path_in_a_subprocess():
+    """With the grid capped far below the tile count every block walks many tiles; the ragged end
+    is then taken by block (tiles mod grid).  Run in a child process because the cap is read once."""
+    import os
+    import subprocess
+    import sys
+    code = r"""
+import sys, os
+sys.path.insert(0, os.getcwd()); sys.path.insert(0, os.path.join(os.getcwd(), "tests"))
+import numpy as np, torch
+import oracle, paper_2209_10778_amd as nfad
+from paper_2209_10778_amd import inputs
+from parity import compare
+for dtype, td in (("f32", torch.float32), ("bf16", torch.bfloat16)):
+    for n in (7 * 2048 * 5 + 333, 40 * 2048 + 1, 13):
+        a = inputs.gaussian(n, 2.0, 4242 + n)
+        x = inputs.to_storage(a, dtype)
+        y_ref, d_ref = oracle.fwd(nfad.MISH, inputs.storage_to_f64(x))
+        xd = x.to("cuda:0")
+        y = torch.full_like(xd, float("nan")); d = torch.full_like(xd, float("nan"))
+        nfad.nfad_fwd(nfad.MISH, xd, y, d)
+        compare(y, y_ref, td, f"stride y {dtype} {n}"); compare(d, d_ref, td, f"stride d {dtype} {n}")
+        gy = inputs.to_storage(inputs.gaussian(n, 1.0, 4343 + n), dtype)
+        dst = inputs.to_storage(d_ref.astype(np.float32), dtype)
+        gx = torch.full_like(xd, float("nan"))
+        nfad.nfad_bwd(gy.to("cuda:0"), dst.to("cuda:0"), gx)
+        compare(gx, oracle.bwd(inputs.storage_to_f64(gy), inputs.storage_to_f64(dst)), td, f"stride gx {dtype} {n}")
+print("stride ok")
+"""
+    env = dict(os.environ, NFAD_MAX_GRID="7")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-c", code], cwd=root, env=env, capture_output=True, text=True, timeout=170)
+    assert r.returncode == 0 and "stride ok" in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
+
+
 def test_beyond_32bit_element_count():
     """n > 2^32 elements (bf16): 64-bit indexing.  The input is a short seeded pattern
     repeated on the device; windows at the start, across 2^31 and 2^32, and at the ragged
