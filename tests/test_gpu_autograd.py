@@ -75,3 +75,25 @@ def test_module_in_a_small_network_trains_a_step():
     ref(x).square().mean().backward()
     for p, q in zip(net.parameters(), ref.parameters()):
         assert torch.allclose(p.grad, q.grad, rtol=2e-4, atol=2e-6)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_non_contiguous_and_16bit_inputs(dtype):
+    td = inputs.TORCH_DTYPE[dtype]
+    a = inputs.to_storage(inputs.gaussian(64 * 48, 1.5, 8400), dtype).view(64, 48)
+    xt = a.to(DEV).t()                                  # a non-contiguous view, logical shape (48, 64)
+    assert not xt.is_contiguous()
+    xd = xt.detach().requires_grad_(True)
+    y = A.mish(xd)
+    assert y.shape == xd.shape
+    gy = inputs.to_storage(inputs.gaussian(48 * 64, 1.0, 8401), dtype).view(48, 64).to(DEV)
+    y.backward(gy)
+    x64 = inputs.storage_to_f64(a.t().contiguous())
+    y_ref, d_ref = oracle.fwd(oracle.MISH, x64)
+    compare(y.detach().contiguous(), y_ref, td, f"non-contiguous y {dtype}")
+    gy64 = inputs.storage_to_f64(gy.cpu()).reshape(-1)
+    g_ref = gy64 * d_ref
+    assert xd.grad.shape == xd.shape
+    # two roundings (dydx, then the product), scaled by |gy|
+    tol = np.abs(gy64) * tolerance(torch.from_numpy(d_ref), td).numpy()
+    compare(xd.grad.contiguous(), g_ref, td, f"non-contiguous grad {dtype}", extra_tol=tol)
