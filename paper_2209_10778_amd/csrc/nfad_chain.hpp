@@ -13,7 +13,7 @@
 // folded away by the compiler (the paper's NY->YN shortcut, Sec. IV-B "Efficiency").
 //
 //   using Mish = Mul<X, Tanh<Softplus<X>>>;          // x * tanh(softplus(x))
-//   Dual r = Mish::eval(seed(x));                    // r.v = y, r.d = dy/dx
+//   Dual r = to_dual(Mish::eval<true>(seed(x)));     // r.v = y, r.d = dy/dx
 //
 // Shared sub-expressions are written twice in the type but evaluated once: everything is
 // inlined and pure, so the compiler merges them.
@@ -31,20 +31,71 @@ struct Dual {
   float v;  // value
   float d;  // tangent d v / d x
 };
+// A value that does not depend on x.  Its tangent is identically zero, and carrying that in
+// the TYPE lets the binary operations with a constant operand (Sec. III-A) drop the dead
+// half of the sum/product/quotient rule: with a run-time 0.0f the compiler may not (0 * inf).
+struct Konst {
+  float v;
+};
 
 __device__ __forceinline__ Dual seed(float x) { return Dual{x, 1.0f}; }
+__device__ __forceinline__ Dual to_dual(Dual a) { return a; }
+__device__ __forceinline__ Dual to_dual(Konst a) { return Dual{a.v, 0.0f}; }
 
 __device__ __forceinline__ float lg2(float v) { return __builtin_amdgcn_logf(v); }  // log2 v
 static constexpr float kLn2 = 0.69314718055994530942f;
 
+// ---------------------------------------------------------------- rules of the binary operations
+__device__ __forceinline__ Dual add_(Dual a, Dual b) { return Dual{a.v + b.v, a.d + b.d}; }
+__device__ __forceinline__ Dual add_(Konst a, Dual b) { return Dual{a.v + b.v, b.d}; }
+__device__ __forceinline__ Dual add_(Dual a, Konst b) { return Dual{a.v + b.v, a.d}; }
+__device__ __forceinline__ Konst add_(Konst a, Konst b) { return Konst{a.v + b.v}; }
+
+__device__ __forceinline__ Dual sub_(Dual a, Dual b) { return Dual{a.v - b.v, a.d - b.d}; }
+__device__ __forceinline__ Dual sub_(Konst a, Dual b) { return Dual{a.v - b.v, -b.d}; }
+__device__ __forceinline__ Dual sub_(Dual a, Konst b) { return Dual{a.v - b.v, a.d}; }
+__device__ __forceinline__ Konst sub_(Konst a, Konst b) { return Konst{a.v - b.v}; }
+
+// product rule: v3' = v1 v2' + v1' v2  (Sec. II-C eq. 3)
+__device__ __forceinline__ Dual mul_(Dual a, Dual b) { return Dual{a.v * b.v, fma_(a.v, b.d, a.d * b.v)}; }
+__device__ __forceinline__ Dual mul_(Konst a, Dual b) { return Dual{a.v * b.v, a.v * b.d}; }
+__device__ __forceinline__ Dual mul_(Dual a, Konst b) { return Dual{a.v * b.v, a.d * b.v}; }
+__device__ __forceinline__ Konst mul_(Konst a, Konst b) { return Konst{a.v * b.v}; }
+
+// quotient rule: (a/b)' = (a' - (a/b) b') / b
+__device__ __forceinline__ Dual div_(Dual a, Dual b) {
+  const float r = rcp(b.v);
+  const float q = a.v * r;
+  return Dual{q, fma_(-q, b.d, a.d) * r};
+}
+__device__ __forceinline__ Dual div_(Konst a, Dual b) {
+  const float r = rcp(b.v);
+  const float q = a.v * r;
+  return Dual{q, (-q * b.d) * r};
+}
+__device__ __forceinline__ Dual div_(Dual a, Konst b) {
+  const float r = rcp(b.v);  // folded at compile time for a literal constant
+  return Dual{a.v * r, a.d * r};
+}
+__device__ __forceinline__ Konst div_(Konst a, Konst b) { return Konst{a.v * rcp(b.v)}; }
+
 // ---------------------------------------------------------------- leaves
+// Every node has   template <bool kWide> static eval(Dual x)   returning Dual or Konst; kWide
+// says that the result will be stored as fp32 (see the tiers in nfad_math.hpp): a few
+// primitives drop a refinement that only shows at fp32 resolution when it is false.
 struct X {  // the source element, tangent 1
-  __device__ __forceinline__ static Dual eval(Dual x) { return x; }
+  template <bool kWide>
+  __device__ __forceinline__ static Dual eval(Dual x) {
+    return x;
+  }
 };
 // A constant: C is any type with `static constexpr float value`.
 template <class C>
 struct Const {
-  __device__ __forceinline__ static Dual eval(Dual) { return Dual{C::value, 0.0f}; }
+  template <bool kWide>
+  __device__ __forceinline__ static Konst eval(Dual) {
+    return Konst{C::value};
+  }
 };
 #define NFAD_CHAIN_CONSTANT(Name, Value) \
   struct Name {                          \
@@ -52,144 +103,139 @@ struct Const {
   }
 
 // ---------------------------------------------------------------- binary, same source
-template <class A, class B>
-struct Add {
-  __device__ __forceinline__ static Dual eval(Dual x) {
-    const Dual a = A::eval(x), b = B::eval(x);
-    return Dual{a.v + b.v, a.d + b.d};
+#define NFAD_CHAIN_BINARY(Name, rule)                                  \
+  template <class A, class B>                                          \
+  struct Name {                                                        \
+    template <bool kWide>                                              \
+    __device__ __forceinline__ static auto eval(Dual x) {              \
+      return rule(A::template eval<kWide>(x), B::template eval<kWide>(x)); \
+    }                                                                  \
   }
-};
-template <class A, class B>
-struct Sub {
-  __device__ __forceinline__ static Dual eval(Dual x) {
-    const Dual a = A::eval(x), b = B::eval(x);
-    return Dual{a.v - b.v, a.d - b.d};
-  }
-};
-template <class A, class B>
-struct Mul {  // product rule: v3' = v1 v2' + v1' v2  (Sec. II-C eq. 3)
-  __device__ __forceinline__ static Dual eval(Dual x) {
-    const Dual a = A::eval(x), b = B::eval(x);
-    return Dual{a.v * b.v, fma_(a.v, b.d, a.d * b.v)};
-  }
-};
-template <class A, class B>
-struct Div {  // (a/b)' = (a' - (a/b) b') / b
-  __device__ __forceinline__ static Dual eval(Dual x) {
-    const Dual a = A::eval(x), b = B::eval(x);
-    const float r = rcp(b.v);
-    const float q = a.v * r;
-    return Dual{q, fma_(-q, b.d, a.d) * r};
-  }
-};
+NFAD_CHAIN_BINARY(Add, add_);
+NFAD_CHAIN_BINARY(Sub, sub_);
+NFAD_CHAIN_BINARY(Mul, mul_);
+NFAD_CHAIN_BINARY(Div, div_);
+#undef NFAD_CHAIN_BINARY
 
 template <class A, class B>
 struct Min {  // the tangent follows the selected operand (the first on a tie)
+  template <bool kWide>
   __device__ __forceinline__ static Dual eval(Dual x) {
-    const Dual a = A::eval(x), b = B::eval(x);
+    const Dual a = to_dual(A::template eval<kWide>(x)), b = to_dual(B::template eval<kWide>(x));
     return a.v <= b.v ? a : (b.v < a.v ? b : Dual{a.v + b.v, a.d + b.d});  // last arm: a NaN stays NaN
   }
 };
 template <class A, class B>
 struct Max {
+  template <bool kWide>
   __device__ __forceinline__ static Dual eval(Dual x) {
-    const Dual a = A::eval(x), b = B::eval(x);
+    const Dual a = to_dual(A::template eval<kWide>(x)), b = to_dual(B::template eval<kWide>(x));
     return a.v >= b.v ? a : (b.v > a.v ? b : Dual{a.v + b.v, a.d + b.d});
   }
 };
 
 // ---------------------------------------------------------------- unary
-template <class A>
-struct Relu {  // max(v, 0); tangent 0 at and below the kink
-  __device__ __forceinline__ static Dual eval(Dual x) {
-    const Dual a = A::eval(x);
-    return a.v > 0.0f ? a : Dual{a.v * 0.0f, a.d * 0.0f};  // v * 0 keeps NaN, gives -0 for v < 0
-  }
-};
-template <class A>
-struct Abs {  // tangent sign(v) v', 0 at the kink
-  __device__ __forceinline__ static Dual eval(Dual x) {
-    const Dual a = A::eval(x);
-    const float sgn = a.v > 0.0f ? 1.0f : (a.v < 0.0f ? -1.0f : a.v * 0.0f);
-    return Dual{__builtin_fabsf(a.v), sgn * a.d};
-  }
-};
-template <class A>
-struct Sqrt {  // (sqrt v)' = v' / (2 sqrt v)
-  __device__ __forceinline__ static Dual eval(Dual x) {
-    const Dual a = A::eval(x);
-    const float r = __builtin_amdgcn_sqrtf(a.v);
-    return Dual{r, (0.5f * a.d) * rcp(r)};
-  }
-};
-template <class A>
-struct Neg {
-  __device__ __forceinline__ static Dual eval(Dual x) {
-    const Dual a = A::eval(x);
-    return Dual{-a.v, -a.d};
-  }
-};
-template <class A>
-struct Exp {
-  __device__ __forceinline__ static Dual eval(Dual x) {
-    const Dual a = A::eval(x);
-    const float e = ex2(kLog2e * a.v);
-    return Dual{e, e * a.d};
-  }
-};
-template <class A>
-struct Log {
-  __device__ __forceinline__ static Dual eval(Dual x) {
-    const Dual a = A::eval(x);
-    return Dual{kLn2 * lg2(a.v), a.d * rcp(a.v)};
-  }
-};
-template <class A>
-struct Sigmoid {  // s' = s (1 - s) = sigmoid(v) sigmoid(-v), both from e = exp(-|v|)
-  __device__ __forceinline__ static Dual eval(Dual x) {
-    const Dual a = A::eval(x);
-    const float e = ex2(-kLog2e * __builtin_fabsf(a.v));
-    const float r = rcp(1.0f + e);
-    const float p = e * r;
-    return Dual{a.v > 0.0f ? r : p, (r * p) * a.d};
-  }
-};
-template <class A>
-struct Tanh {  // tanh v = sign(v) (1 - e)/(1 + e), 1 - tanh^2 = 4 e/(1 + e)^2, e = exp(-2|v|)
-  __device__ __forceinline__ static Dual eval(Dual x) {
-    const Dual a = A::eval(x);
-    const float av = __builtin_fabsf(a.v);
-    const float e = ex2((-2.0f * kLog2e) * av);
-    const float r = rcp(1.0f + e);
-    // for tiny |v| the quotient (1-e)/(1+e) would lose relative accuracy: tanh v = v - v^3/3 there
+// Each rule maps the operand's (value, tangent) to the result's; NFAD_CHAIN_UNARY wraps it
+// into a node.
+__device__ __forceinline__ Dual relu_(Dual a) {  // max(v, 0); tangent 0 at and below the kink
+  return a.v > 0.0f ? a : Dual{a.v * 0.0f, a.d * 0.0f};  // v * 0 keeps NaN, gives -0 for v < 0
+}
+__device__ __forceinline__ Dual abs_(Dual a) {  // tangent sign(v) v', 0 at the kink
+  const float sgn = a.v > 0.0f ? 1.0f : (a.v < 0.0f ? -1.0f : a.v * 0.0f);
+  return Dual{__builtin_fabsf(a.v), sgn * a.d};
+}
+__device__ __forceinline__ Dual sqrt_(Dual a) {  // (sqrt v)' = v' / (2 sqrt v)
+  const float r = __builtin_amdgcn_sqrtf(a.v);
+  return Dual{r, (0.5f * a.d) * rcp(r)};
+}
+__device__ __forceinline__ Dual neg_(Dual a) { return Dual{-a.v, -a.d}; }
+__device__ __forceinline__ Dual exp_(Dual a) {
+  const float e = ex2(kLog2e * a.v);
+  return Dual{e, e * a.d};
+}
+__device__ __forceinline__ Dual log_(Dual a) { return Dual{kLn2 * lg2(a.v), a.d * rcp(a.v)}; }
+__device__ __forceinline__ Dual sigmoid_(Dual a) {  // s' = s (1 - s) = sigmoid(v) sigmoid(-v), both from e = exp(-|v|)
+  const float e = ex2(-kLog2e * __builtin_fabsf(a.v));
+  const float r = rcp(1.0f + e);
+  const float p = e * r;
+  return Dual{a.v > 0.0f ? r : p, (r * p) * a.d};
+}
+template <bool kWide>
+__device__ __forceinline__ Dual tanh_(Dual a) {  // tanh v = sign(v) (1 - e)/(1 + e), 1 - tanh^2 = 4 e/(1 + e)^2, e = exp(-2|v|)
+  const float av = __builtin_fabsf(a.v);
+  const float e = ex2((-2.0f * kLog2e) * av);
+  const float r = rcp(1.0f + e);
+  const float big = __builtin_copysignf((1.0f - e) * r, a.v);
+  const float dt = (4.0f * e) * (r * r) * a.d;
+  if constexpr (kWide) {
+    // for tiny |v| the quotient (1-e)/(1+e) loses relative accuracy (its absolute error stays
+    // at the fp32 ulp of 1, which 16-bit storage cannot see): tanh v = v - v^3/3 there
     const float small = a.v * fma_(a.v * a.v, -0.33333333f, 1.0f);
-    const float big = __builtin_copysignf((1.0f - e) * r, a.v);
-    return Dual{av < 0.03125f ? small : big, (4.0f * e) * (r * r) * a.d};
+    return Dual{av < 0.03125f ? small : big, dt};
+  } else {
+    return Dual{big, dt};
   }
-};
-template <class A>
-struct Softplus {  // ln(1 + e^v) = max(v, 0) + log1p(exp(-|v|)),  softplus' = sigmoid
-  __device__ __forceinline__ static Dual eval(Dual x) {
-    const Dual a = A::eval(x);
-    const float e = ex2(-kLog2e * __builtin_fabsf(a.v));
-    // log1p(e): e - e^2/2 while 1 + e would round e away, log2(1 + e) ln 2 otherwise
-    const float l1p = e < 0.0009765625f ? e * fma_(-0.5f, e, 1.0f) : kLn2 * lg2(1.0f + e);
-    const float r = rcp(1.0f + e);
-    return Dual{__builtin_fmaxf(a.v, 0.0f) + l1p, (a.v > 0.0f ? r : e * r) * a.d};
+}
+template <bool kWide>
+__device__ __forceinline__ Dual softplus_(Dual a) {  // ln(1 + e^v) = max(v, 0) + log1p(exp(-|v|)),  softplus' = sigmoid
+  const float e = ex2(-kLog2e * __builtin_fabsf(a.v));
+  float l1p = kLn2 * lg2(1.0f + e);
+  // log1p(e) = e - e^2/2 where 1 + e would round e away (an absolute error of at most 2^-24, again
+  // invisible after rounding to 16 bits next to max(v, 0) or below the smallest fp16 normal)
+  if constexpr (kWide) l1p = e < 0.0009765625f ? e * fma_(-0.5f, e, 1.0f) : l1p;
+  const float r = rcp(1.0f + e);
+  return Dual{__builtin_fmaxf(a.v, 0.0f) + l1p, (a.v > 0.0f ? r : e * r) * a.d};
+}
+__device__ __forceinline__ Dual erf_(Dual a) {  // erf' = 2/sqrt(pi) exp(-v^2)
+  const float s = 1.41421356237309504880f * __builtin_fabsf(a.v);
+  const float E = ex2((-0.5f * kLog2e) * (s * s));  // exp(-v^2)
+  const float erfc_a = 2.0f * half_erfcx<ErfcxWide>(s) * E;
+  // small |v|: 1 - erfc cancels; use the series 2/sqrt(pi) (v - v^3/3 + v^5/10)
+  const float v2 = a.v * a.v;
+  const float series = 1.12837916709551257390f * a.v * fma_(v2, fma_(v2, 0.1f, -0.33333333f), 1.0f);
+  const float big = __builtin_copysignf(1.0f - erfc_a, a.v);
+  return Dual{__builtin_fabsf(a.v) < 0.125f ? series : big, (1.12837916709551257390f * E) * a.d};
+}
+// tanh(softplus(v)) in one step: with e = exp(v) and n = e (e + 2) it is n / (n + 2), and its
+// derivative is 4 e (e + 1) / (n + 2)^2: one exponential and one reciprocal instead of two
+// exponentials, a logarithm and two reciprocals.  v is capped at 41.5 inside the exponential
+// (the result is 1 and its derivative 0 to fp32 precision far below that) so that n stays
+// finite; the cap is a compare-and-select so that NaN stays NaN.
+__device__ __forceinline__ Dual tanh_softplus_(Dual a) {
+  const float vc = mish_cap(a.v);
+  const float e = ex2(kLog2e * vc);
+  const float n = fma_(e, e, e + e);
+  const float R = rcp(n + 2.0f);
+  const float g = fma_(4.0f, e, 4.0f) * e;
+  return Dual{n * R, (g * R) * R * a.d};
+}
+
+#define NFAD_CHAIN_UNARY(Name, rule)                                \
+  template <class A>                                                \
+  struct Name {                                                     \
+    template <bool kWide>                                           \
+    __device__ __forceinline__ static Dual eval(Dual x) {           \
+      return rule(to_dual(A::template eval<kWide>(x)));             \
+    }                                                               \
   }
-};
+NFAD_CHAIN_UNARY(Relu, relu_);
+NFAD_CHAIN_UNARY(Abs, abs_);
+NFAD_CHAIN_UNARY(Sqrt, sqrt_);
+NFAD_CHAIN_UNARY(Neg, neg_);
+NFAD_CHAIN_UNARY(Exp, exp_);
+NFAD_CHAIN_UNARY(Log, log_);
+NFAD_CHAIN_UNARY(Sigmoid, sigmoid_);
+NFAD_CHAIN_UNARY(Tanh, tanh_<kWide>);
+NFAD_CHAIN_UNARY(Softplus, softplus_<kWide>);
+NFAD_CHAIN_UNARY(Erf, erf_);
+#undef NFAD_CHAIN_UNARY
+
+// Fused pair (the composer's one peephole): tanh directly on a softplus, the core of Mish.
 template <class A>
-struct Erf {  // erf' = 2/sqrt(pi) exp(-v^2)
+struct Tanh<Softplus<A>> {
+  template <bool kWide>
   __device__ __forceinline__ static Dual eval(Dual x) {
-    const Dual a = A::eval(x);
-    const float s = 1.41421356237309504880f * __builtin_fabsf(a.v);
-    const float E = ex2((-0.5f * kLog2e) * (s * s));  // exp(-v^2)
-    const float erfc_a = 2.0f * half_erfcx<ErfcxWide>(s) * E;
-    // small |v|: 1 - erfc cancels; use the series 2/sqrt(pi) (v - v^3/3 + v^5/10)
-    const float v2 = a.v * a.v;
-    const float series = 1.12837916709551257390f * a.v * fma_(v2, fma_(v2, 0.1f, -0.33333333f), 1.0f);
-    const float big = __builtin_copysignf(1.0f - erfc_a, a.v);
-    return Dual{__builtin_fabsf(a.v) < 0.125f ? series : big, (1.12837916709551257390f * E) * a.d};
+    return tanh_softplus_(to_dual(A::template eval<kWide>(x)));
   }
 };
 
@@ -202,7 +248,7 @@ struct ChainFwdOp {
   static constexpr int kIn = 1, kOut = 2;
   template <bool kWide>
   __device__ __forceinline__ static void apply(const float (&in)[kIn], float (&out)[kOut]) {
-    const chain::Dual r = Chain::eval(chain::seed(in[0]));
+    const chain::Dual r = chain::to_dual(Chain::template eval<kWide>(chain::seed(in[0])));
     out[0] = r.v;
     out[1] = r.d;
   }
@@ -215,7 +261,7 @@ struct ChainFwdMultiOp {
   static constexpr int kIn = 1, kOut = 2 * (int)sizeof...(Chains);
   template <bool kWide>
   __device__ __forceinline__ static void apply(const float (&in)[kIn], float (&out)[kOut]) {
-    const chain::Dual r[] = {Chains::eval(chain::seed(in[0]))...};
+    const chain::Dual r[] = {chain::to_dual(Chains::template eval<kWide>(chain::seed(in[0])))...};
 #pragma unroll
     for (int m = 0; m < (int)sizeof...(Chains); ++m) {
       out[2 * m] = r[m].v;

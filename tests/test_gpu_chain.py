@@ -95,6 +95,11 @@ JIT_PROGRAMS = [
     "x relu 1.5 x 0 min exp 1 - * +",           # ELU with alpha = 1.5
     "x abs 1 + sqrt x *",                       # x sqrt(1 + |x|)
     "x -1 max 2.5 min x *",                     # x clamp(x, -1, 2.5)
+    "x 0.75 * softplus tanh 2 *",               # the fused tanh-of-softplus pair on a scaled operand
+    "2 x exp 1 + /",                            # constant / chain
+    "x 3 / x -",                                # chain / constant
+    "3 x - tanh",                               # constant - chain
+    "x 1 2 + 4 * 8 / 0.5 - *",                  # a constant sub-expression: x * ((1 + 2) * 4 / 8 - 0.5)
 ]
 
 
