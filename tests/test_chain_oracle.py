@@ -101,3 +101,67 @@ def test_saturation_of_symbolic_primitives():
     for prog in ("x sigmoid", "x tanh", "x softplus", "x sigmoid x *", "x x softplus tanh *"):
         y, d = chain.eval_chain(prog, x)
         assert np.all(np.isfinite(y)) and np.all(np.isfinite(d)), prog
+
+
+# ------------------------------------------------------------------ random compositions
+def mp_eval(program, x):
+    """The program's value at the mpmath number x (a second, value-only reading of the postfix
+    grammar; the tangent is NOT propagated here: it comes from numerical differentiation)."""
+    un = {"neg": lambda a: -a, "exp": mp.exp, "log": mp.log, "tanh": mp.tanh,
+          "sigmoid": lambda a: 1 / (1 + mp.exp(-a)), "softplus": lambda a: mp.log(1 + mp.exp(a)),
+          "erf": mp.erf, "relu": lambda a: a if a > 0 else mp.mpf(0), "abs": abs, "sqrt": mp.sqrt}
+    bi = {"+": lambda a, b: a + b, "-": lambda a, b: a - b, "*": lambda a, b: a * b, "/": lambda a, b: a / b,
+          "min": min, "max": max}
+    st = []
+    for tok in program.split():
+        if tok == "x":
+            st.append(x)
+        elif tok in un:
+            st.append(un[tok](st.pop()))
+        elif tok in bi:
+            b = st.pop()
+            a = st.pop()
+            st.append(bi[tok](a, b))
+        else:
+            st.append(mp.mpf(tok))
+    assert len(st) == 1
+    return st[0]
+
+
+def test_interpreter_matches_mpmath_on_random_compositions():
+    """Forty random chains over all primitives: value against the mpmath evaluation, tangent
+    against numerical differentiation at 50 digits; points where the two one-sided derivatives
+    differ (a kink of relu/abs/min/max) are skipped."""
+    from chain_programs import random_programs
+    xs = np.array([-5.43, -4.37, -1.913, -0.577, -0.0731, 0.318, 1.234, 2.718, 5.77])
+    checked = 0
+    for program in random_programs(40):
+        y, d = chain.eval_chain(program, xs)
+        f = lambda t: mp_eval(program, t)
+        for i, xv in enumerate(xs):
+            xm = mp.mpf(float(xv))
+            left, right = mp.diff(f, xm, direction=-1, h=mp.mpf(10) ** -20), mp.diff(f, xm, direction=1, h=mp.mpf(10) ** -20)
+            if abs(left - right) > mp.mpf(10) ** -12:
+                continue
+            yr, dr = f(xm), (left + right) / 2
+            assert abs(float(yr) - y[i]) <= 2e-14 * max(1.0, abs(float(yr))), (program, "y", xv)
+            assert abs(float(dr) - d[i]) <= 2e-13 * max(1.0, abs(float(dr))), (program, "d", xv)
+            checked += 1
+    assert checked > 300
+
+
+@pytest.mark.parametrize("token", sorted(chain._UNARY) + sorted(chain._BINARY))
+def test_a_planted_tangent_mistake_in_any_rule_is_caught(token, monkeypatch):
+    """Each primitive's rule in turn gets its tangent scaled by 1.001 (or, for the selecting
+    rules, taken from the other operand); the random-composition pin must then fail."""
+    table = chain._UNARY if token in chain._UNARY else chain._BINARY
+    good = table[token]
+    if token in ("min", "max"):
+        bad = lambda a, da, b, db: (good(a, da, b, db)[0], good(a, db, b, da)[1])
+    elif token in ("relu", "abs"):
+        bad = lambda v, d: (good(v, d)[0], d)
+    else:
+        bad = lambda *args: (good(*args)[0], 1.001 * good(*args)[1])
+    monkeypatch.setitem(table, token, bad)
+    with pytest.raises(AssertionError):
+        test_interpreter_matches_mpmath_on_random_compositions()

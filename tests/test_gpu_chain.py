@@ -8,6 +8,7 @@ from oracle import chain
 import oracle
 import paper_2209_10778_amd as nfad
 from paper_2209_10778_amd import inputs
+from chain_programs import random_programs
 from parity import compare
 
 pytestmark = pytest.mark.gpu
@@ -186,3 +187,26 @@ def test_multi_output_autograd_front_end():
     d1 = chain.eval_chain(programs[0], x64)[1]
     d2 = chain.eval_chain(programs[1], x64)[1]
     compare(xd.grad, d1 + 2.0 * d2, torch.float32, "multi autograd", extra_tol=1e-5 * np.maximum(1, np.abs(x64)))
+
+
+# ------------------------------------------------------------------ random programs
+def test_random_programs_match_interpreter():
+    """Thirty seeded random chains, compiled at run time, against the interpreter (fp32 and fp16)."""
+    programs = random_programs(30)
+    a = np.clip(inputs.gaussian(N, 2.0, 7600), -6.0, 6.0)
+    for prog in programs:
+        cid = nfad.nfad_chain_compile(prog)
+        for dtype in ("f32", "f16"):
+            td = DTYPES[dtype]
+            x = inputs.to_storage(a, dtype)
+            x64 = inputs.storage_to_f64(x)
+            y_ref, d_ref = chain.eval_chain(prog, x64)
+            assert np.isfinite(y_ref).all() and np.isfinite(d_ref).all(), prog
+            xd = x.to(DEV)
+            y = torch.full_like(xd, float("nan"))
+            d = torch.full_like(xd, float("nan"))
+            nfad.nfad_chain_fwd(cid, xd, y, d)
+            rel = 2e-6 * np.maximum(1.0, np.abs(x64)) ** 2
+            compare(y, y_ref, td, f"random {prog!r} y {dtype}", extra_tol=rel * np.maximum(1.0, np.abs(y_ref)))
+            compare(d, d_ref, td, f"random {prog!r} dydx {dtype}", extra_tol=rel * np.maximum(1.0, np.abs(d_ref)))
+        nfad.nfad_chain_release(cid)
