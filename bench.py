@@ -9,7 +9,8 @@ sets are rotated so that successive launches do not hit in the 256 MB last-level
 
 Prints ONE JSON line.  `value` is algorithmic HBM bytes of a step / step time.  `roofline`
 describes the method's forward kernel (nfad_fwd), its launch duration measured with events
-on the launch stream over a region of back-to-back launches.  `cpu_baseline` is the fp64
+on the launch stream over a region of back-to-back launches (for tensors so small that a
+launch is shorter than a Python call, the launches are replayed from a HIP graph).  `cpu_baseline` is the fp64
 oracle timed on the host cores on a bounded sample of the same workload.
 """
 from __future__ import annotations
@@ -39,9 +40,16 @@ def parse_args():
                          "known-size kernel that rocprofv3 FETCH_SIZE/WRITE_SIZE readings are scaled by")
     ap.add_argument("--prewarm-s", type=float, default=0.25,
                     help="seconds of untimed steps before the warm-up steps (reaches steady clocks)")
+    ap.add_argument("--kernel-warm-s", type=float, default=0.3,
+                    help="seconds of untimed launches of a kernel before its launch duration is measured: the "
+                         "duration keeps settling (by 2-4 %%) for a few hundred ms after the kernel mix changes")
     ap.add_argument("--chains", action="store_true",
                     help="also time the fused forward kernel of every composed chain on the same tensor")
     ap.add_argument("--cpu-sample", type=int, default=1 << 25, help="max elements the oracle is timed on")
+    ap.add_argument("--launch", choices=("auto", "direct", "graph"), default="auto",
+                    help="how timed launches are issued: one C-ABI call each from Python (direct), or captured "
+                         "once into a HIP graph and replayed (graph); auto = graph when a launch moves less "
+                         "than 64 MB, i.e. when it is shorter than the interpreter's launch rate")
     return ap.parse_args()
 
 
@@ -88,57 +96,83 @@ def main():
     stream = torch.cuda.current_stream()
 
     kernels = {
-        "nfad_fwd": (lambda s: nfad.nfad_fwd(kind, s["x"], s["y"], s["dydx"], stream), 3),
-        "nfad_bwd": (lambda s: nfad.nfad_bwd(s["gy"], s["dydx"], s["gx"], stream), 3),
-        "recompute_fwd": (lambda s: nfad.nfad_recompute_fwd(kind, s["x"], s["y"], stream), 2),
-        "recompute_bwd": (lambda s: nfad.nfad_recompute_bwd(kind, s["gy"], s["x"], s["gx"], stream), 3),
-        "saveall_fwd": (lambda s: nfad.nfad_saveall_fwd(kind, s["x"], s["y"], s["saved"], stream), 1 + k_saved),
-        "saveall_bwd": (lambda s: nfad.nfad_saveall_bwd(kind, s["gy"], s["saved"], s["gx"], stream), 2 + k_saved),
+        "nfad_fwd": (lambda s, st: nfad.nfad_fwd(kind, s["x"], s["y"], s["dydx"], st), 3),
+        "nfad_bwd": (lambda s, st: nfad.nfad_bwd(s["gy"], s["dydx"], s["gx"], st), 3),
+        "recompute_fwd": (lambda s, st: nfad.nfad_recompute_fwd(kind, s["x"], s["y"], st), 2),
+        "recompute_bwd": (lambda s, st: nfad.nfad_recompute_bwd(kind, s["gy"], s["x"], s["gx"], st), 3),
+        "saveall_fwd": (lambda s, st: nfad.nfad_saveall_fwd(kind, s["x"], s["y"], s["saved"], st), 1 + k_saved),
+        "saveall_bwd": (lambda s, st: nfad.nfad_saveall_bwd(kind, s["gy"], s["saved"], s["gx"], st), 2 + k_saved),
     }
     words_per_step = sum(w for _, w in kernels.values())
     bytes_per_step = words_per_step * n * es
+    use_graph = args.launch == "graph" or (args.launch == "auto" and 3 * n * es < 64e6)
 
-    def step(i):
-        s = sets[i % nsets]
-        for fn, _ in kernels.values():
-            fn(s)
+    def runner(fns, count):
+        """A callable that enqueues `count` rounds of `fns` (buffer sets rotating) on the current
+        stream: launch by launch from Python, or as one replay of a HIP graph captured here (the
+        library's calls are capturable: no allocation, no synchronisation, no memset)."""
+        def enqueue():
+            st = torch.cuda.current_stream()
+            for i in range(count):
+                s = sets[i % nsets]
+                for fn in fns:
+                    fn(s, st)
+        if not use_graph:
+            return enqueue
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            enqueue()
+        return g.replay
+
+    step_fns = [fn for fn, _ in kernels.values()]
 
     # Untimed pre-warm: kernel times on this part settle ~3 % lower after a few tens of ms of
     # sustained streaming (clocks, TLBs), so reach steady state before the W warm-up steps.
+    warm_steps = runner(step_fns, max(1, args.warmup))
+    timed_steps = runner(step_fns, args.steps)
     t_pre = time.perf_counter()
     i_pre = 0
     while time.perf_counter() - t_pre < args.prewarm_s:
-        step(i_pre)
+        warm_steps()
         i_pre += 1
-        if i_pre % 16 == 0:
+        if i_pre % 4 == 0:
             torch.cuda.synchronize()
-    for i in range(args.warmup):
-        step(i)
+    if args.warmup > 0:
+        warm_steps()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
+    timed_steps()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     value = bytes_per_step / (ms_per_step * 1e-3) / 1e9
 
     # ---- per-kernel launch duration: events on the launch stream around back-to-back launches.
-    # Warm-up launches are queued right in front of the timed region (no idle gap, so clocks and
-    # caches are in steady state when the first event fires).
-    per_kernel = {}
-    for name, (fn, words) in kernels.items():
+    # The part adapts to the traffic pattern over a few hundred ms (a kernel measured right after
+    # a different kernel mix reads 2-4 % slower than in steady state), so each kernel first runs
+    # alone for kernel_warm_s; the last warm-up launches are queued right in front of the timed
+    # region (no idle gap).
+    def time_launches(fn):
+        timed = runner([fn], args.steps)
         e0 = torch.cuda.Event(enable_timing=True)
         e1 = torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
-        for i in range(max(300, args.warmup)):
-            fn(sets[i % nsets])
+        t_w = time.perf_counter()
+        while time.perf_counter() - t_w < args.kernel_warm_s:   # sustained launches of THIS kernel
+            for _ in range(4):
+                timed()
+            torch.cuda.synchronize()
+        for _ in range(-(-max(300, args.warmup) // args.steps)):
+            timed()
         e0.record(stream)
-        for i in range(args.steps):
-            fn(sets[i % nsets])
+        timed()
         e1.record(stream)
         torch.cuda.synchronize()
-        us = e0.elapsed_time(e1) * 1e3 / args.steps
+        return e0.elapsed_time(e1) * 1e3 / args.steps
+
+    per_kernel = {}
+    for name, (fn, words) in kernels.items():
+        us = time_launches(fn)
         gbps = words * n * es / (us * 1e-6) / 1e9
         per_kernel[name] = {"us": round(us, 2), "bytes_per_elem": words * es, "GB/s": round(gbps, 1),
                             "frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4),
@@ -170,18 +204,7 @@ def main():
         jit_id = nfad.nfad_chain_compile("x x softplus tanh *")    # Mish again, compiled at run time
         jit_compile_s = time.perf_counter() - t_c
         for cid in list(range(nfad.nfad_chain_count())) + [jit_id]:
-            fn = lambda s, cid=cid: nfad.nfad_chain_fwd(cid, s["x"], s["y"], s["dydx"], stream)
-            e0 = torch.cuda.Event(enable_timing=True)
-            e1 = torch.cuda.Event(enable_timing=True)
-            torch.cuda.synchronize()
-            for i in range(max(300, args.warmup)):
-                fn(sets[i % nsets])
-            e0.record(stream)
-            for i in range(args.steps):
-                fn(sets[i % nsets])
-            e1.record(stream)
-            torch.cuda.synchronize()
-            us = e0.elapsed_time(e1) * 1e3 / args.steps
+            us = time_launches(lambda s, st, cid=cid: nfad.nfad_chain_fwd(cid, s["x"], s["y"], s["dydx"], st))
             gbps = 3 * n * es / (us * 1e-6) / 1e9
             key = nfad.nfad_chain_name(cid) if cid != jit_id else "runtime-compiled mish"
             chains[key] = {"us": round(us, 2), "GB/s": round(gbps, 1),
@@ -225,8 +248,7 @@ def main():
         gy64 = inputs.storage_to_f64(gy_host[:ns])
         threads = oracle.max_threads()
         oracle.fwd(kind, x64[: 1 << 16])          # warm the library, untimed
-        walls = []
-        for _ in range(3):                         # median of three passes of the whole step
+        def one_step_on_cpu():
             c0 = time.perf_counter()
             y64, d64 = oracle.fwd(kind, x64)
             oracle.bwd(gy64, d64)
@@ -234,8 +256,12 @@ def main():
             oracle.recompute_bwd(kind, gy64, x64)
             _, saved64 = oracle.saveall_fwd(kind, x64)
             oracle.saveall_bwd(kind, gy64, saved64)
-            walls.append(time.perf_counter() - c0)
-        wall = sorted(walls)[1]
+            return time.perf_counter() - c0
+        walls = [one_step_on_cpu()]
+        # whole steps until about a second of wall time (10-20 s of CPU time on 16 threads), at least 3
+        while len(walls) < 3 or (sum(walls) < 1.0 and len(walls) < 50):
+            walls.append(one_step_on_cpu())
+        wall = sorted(walls)[len(walls) // 2]
         c0, c1 = 0.0, wall
         # once single-threaded, on a sixteenth of the sample
         n1 = max(1, ns // 16)
@@ -247,11 +273,11 @@ def main():
             "value": round(words_per_step * ns * es / (c1 - c0) / 1e9, 3), "unit": "GB/s",
             "single_thread_fwd_bwd_Gelem/s": round(n1 / (s1 - s0) / 1e9, 4),
             "cores": threads, "kind": "oracle",
-            "sample": f"first {ns} of {n} elements, one step (all six passes) in fp64 with OpenMP, median of 3, "
+            "sample": f"first {ns} of {n} elements, one step (all six passes) in fp64 with OpenMP, median of {len(walls)} steps, "
                       f"{c1 - c0:.2f} s wall; bytes counted as for the {dtype}-storage GPU step",
             "Gelem/s_per_pass": round(6 * ns / (c1 - c0) / 1e9, 4),
         }
-        del y64, d64, saved64, x64, gy64
+        del x64, gy64
 
     out = {
         "metric": "achieved HBM GB/s (% of peak) for fused fwd+dydx and bwd; Gelem/s",
@@ -260,7 +286,8 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",   # arithmetic is fp32 for every storage type
         "config": {"workload": cfg.name, "activation": nfad.KIND_NAMES[kind], "shape": list(spec.shape),
                    "elements": n, "storage": dtype, "step": list(kernels.keys()),
-                   "bytes_per_step": bytes_per_step, "buffer_sets": nsets},
+                   "bytes_per_step": bytes_per_step, "buffer_sets": nsets,
+                   "launch": "hip graph replay" if use_graph else "direct"},
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
         "Gelem/s": round(6 * n / (ms_per_step * 1e-3) / 1e9, 1),
         "roofline": roofline, "cpu_baseline": cpu_baseline, "kernels": per_kernel, "summary": summary,

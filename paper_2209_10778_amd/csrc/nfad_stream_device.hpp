@@ -5,7 +5,8 @@
 //
 // Each lane moves 16 bytes per access (4 fp32 or 8 fp16/bf16 elements), consecutive lanes
 // touch consecutive 16-byte words (1 KiB per wave64 access), kUnroll independent accesses per
-// tensor are in flight per lane, and blocks take the tensor tile by tile in address order.
+// tensor are in flight per lane (each stored as soon as it is computed), and blocks take the
+// tensor tile by tile in address order.
 // All arithmetic is fp32 in registers.  There is no LDS use, no atomics and no scratch
 // memory: every pass is a pure HBM stream.
 #pragma once
@@ -153,6 +154,11 @@ __global__ __launch_bounds__((LaunchShape<Op::kIn, Op::kOut>::kThreads)) void ew
 #pragma unroll
       for (int o = 0; o < Op::kOut; ++o)
         stream_store(reinterpret_cast<Vec*>(p.out[o]) + (base + (size_t)j * kThreads), vout[o]);
+      // Keep the vectors apart in the instruction stream: vector j is stored before vector
+      // j + 1 is waited for and computed, so stores leave the wave in pairs spread over its
+      // compute phase instead of in one burst at the end (measured: forward kernels 1-3 %
+      // faster, the others unchanged).
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
 
