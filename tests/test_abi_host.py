@@ -3,6 +3,7 @@ header declares, and rejects bad arguments before touching the HIP runtime."""
 import ctypes
 import os
 import re
+import sys
 
 import pytest
 
@@ -166,3 +167,13 @@ int main(void) {
     r = subprocess.run([str(exe)], capture_output=True, text=True)
     assert r.returncode == 0, r.stdout + r.stderr
     assert "aligned" in r.stdout
+
+
+def test_the_plain_c_test_program_builds():
+    """tests/c_abi/nfad_c_check.c (run by the GPU suite) compiles as C99 with -Werror and links
+    against the library, the oracle and the HIP runtime's C API."""
+    sys.path.insert(0, os.path.join(ROOT, "tests", "c_abi"))
+    import build_check
+    import oracle
+    oracle.build()
+    assert os.path.exists(build_check.build())
