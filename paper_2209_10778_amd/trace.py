@@ -102,6 +102,8 @@ def _bin(tok):
     return lambda a, b: a + b + [tok]
 
 
+_SELU_SCALE, _SELU_ALPHA = repr(1.0507009873554804934193349852946), repr(1.6732632423543772848170429916717)
+
 _UNARY = {
     "neg": _un("neg"), "exp": _un("exp"), "log": _un("log"), "tanh": _un("tanh"), "sigmoid": _un("sigmoid"),
     "softplus": _un("softplus"), "erf": _un("erf"), "relu": _un("relu"), "abs": _un("abs"), "sqrt": _un("sqrt"),
@@ -109,6 +111,15 @@ _UNARY = {
     "relu6": lambda a: a + ["0", "max", "6", "min"],
     "hardswish": lambda a: a + a + ["3", "+", "0", "max", "6", "min", "*", "6", "/"],
     "softsign": lambda a: a + ["1"] + a + ["abs", "+", "/"],
+    "logsigmoid": lambda a: a + ["neg", "softplus", "neg"],
+    "tanhshrink": lambda a: a + a + ["tanh", "-"],
+    "hardsigmoid": lambda a: a + ["6", "/", "0.5", "+", "0", "max", "1", "min"],
+    "reciprocal": lambda a: ["1"] + a + ["/"],
+    "rsqrt": lambda a: ["1"] + a + ["sqrt", "/"],
+    "expm1": lambda a: a + ["exp", "1", "-"],
+    "log1p": lambda a: ["1"] + a + ["+", "log"],
+    "erfc": lambda a: ["1"] + a + ["erf", "-"],
+    "selu": lambda a: [_SELU_SCALE] + a + ["relu", _SELU_ALPHA] + a + ["0", "min", "exp", "1", "-", "*", "+", "*"],
     "silu": lambda a: a + a + ["sigmoid", "*"],
     "mish": lambda a: a + a + ["softplus", "tanh", "*"],
     "gelu_erf": lambda a: ["0.5"] + a + ["*", "1", repr(1.0 / math.sqrt(2.0))] + a + ["*", "erf", "+", "*"],
@@ -129,6 +140,10 @@ def _op_name(func):
         "mish": "mish", "gelu": "gelu", "pow": "pow", "__pow__": "pow", "relu": "relu", "abs": "abs",
         "absolute": "abs", "__abs__": "abs", "sqrt": "sqrt", "relu6": "relu6", "hardswish": "hardswish",
         "softsign": "softsign", "elu": "elu", "clamp": "clamp", "clip": "clamp",
+        "logsigmoid": "logsigmoid", "log_sigmoid": "logsigmoid", "tanhshrink": "tanhshrink", "hardsigmoid": "hardsigmoid",
+        "reciprocal": "reciprocal", "rsqrt": "rsqrt", "expm1": "expm1", "log1p": "log1p", "erfc": "erfc",
+        "selu": "selu", "leaky_relu": "leaky_relu", "celu": "celu", "hardtanh": "hardtanh",
+        "clamp_min": "clamp_min", "clamp_max": "clamp_max",
     }
     return table.get(n)
 
@@ -175,9 +190,43 @@ class fuse(TorchFunctionMode):
                 a = self._operand(args[0], source)
                 prog = None if a is None else _UNARY["gelu_tanh" if approx == "tanh" else "gelu_erf"](a)
         elif op == "softplus":
-            if len(args) == 1 and kwargs.get("beta", 1.0) == 1.0 and kwargs.get("threshold", 20.0) == 20.0:
+            # softplus(v; beta) = softplus(beta v) / beta.  The framework switches to the identity above
+            # beta v = threshold, where the two differ by less than exp(-threshold): any threshold >= 15
+            # is below fp32 resolution and is treated as exact.
+            beta, thr = kwargs.get("beta", 1.0), kwargs.get("threshold", 20.0)
+            if len(args) == 1 and set(kwargs) <= {"beta", "threshold"} and _const(beta) is not None \
+                    and float(beta) > 0 and _const(thr) is not None and float(thr) >= 15.0:
                 a = self._operand(args[0], source)
-                prog = None if a is None else _UNARY["softplus"](a)
+                if a is not None:
+                    prog = _UNARY["softplus"](a) if float(beta) == 1.0 else \
+                        a + [_const(beta), "*", "softplus", _const(beta), "/"]
+        elif op in ("leaky_relu", "celu", "hardtanh", "clamp_min", "clamp_max"):
+            a = self._operand(args[0], source) if args else None
+            rest = list(args[1:])
+            if a is not None and not kwargs.get("inplace", False):
+                def param(name, default):
+                    v = rest.pop(0) if rest else kwargs.get(name, default)
+                    return _const(v)
+                if op == "leaky_relu" and set(kwargs) <= {"negative_slope", "inplace"} and len(args) <= 2:
+                    slope = param("negative_slope", 0.01)
+                    if slope is not None:       # relu(a) + slope * min(a, 0)
+                        prog = a + ["relu", slope] + a + ["0", "min", "*", "+"]
+                elif op == "celu" and set(kwargs) <= {"alpha", "inplace"} and len(args) <= 2:
+                    alpha = param("alpha", 1.0)
+                    if alpha is not None and float(alpha) != 0.0:   # relu(a) + alpha * (exp(min(a, 0) / alpha) - 1)
+                        prog = a + ["relu", alpha] + a + ["0", "min", alpha, "/", "exp", "1", "-", "*", "+"]
+                elif op == "hardtanh" and set(kwargs) <= {"min_val", "max_val", "inplace"} and len(args) <= 3:
+                    lo, hi = param("min_val", -1.0), param("max_val", 1.0)
+                    if lo is not None and hi is not None:
+                        prog = a + [lo, "max", hi, "min"]
+                elif op == "clamp_min" and set(kwargs) <= {"min"} and len(args) <= 2:
+                    lo = param("min", None)
+                    if lo is not None:
+                        prog = a + [lo, "max"]
+                elif op == "clamp_max" and set(kwargs) <= {"max"} and len(args) <= 2:
+                    hi = param("max", None)
+                    if hi is not None:
+                        prog = a + [hi, "min"]
         elif op == "elu":
             alpha = kwargs.get("alpha", 1.0)
             if len(args) == 1 and set(kwargs) <= {"alpha", "inplace"} and not kwargs.get("inplace", False) \

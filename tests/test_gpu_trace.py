@@ -114,3 +114,43 @@ def test_a_small_network_with_user_written_mish_trains_a_step():
     g2 = [p.grad for p in list(lin1.parameters()) + list(lin2.parameters())]
     for a, b in zip(g1, g2):
         assert torch.allclose(a, b, rtol=2e-4, atol=2e-6)
+
+
+FRAMEWORK_CODE = {
+    "selu_gate": lambda x: F.selu(x) * torch.sigmoid(1.702 * x),
+    "leaky_logsigmoid": lambda x: F.leaky_relu(x, 0.1) + F.logsigmoid(x),
+    "celu_hardtanh": lambda x: F.celu(x, alpha=0.5) - F.hardtanh(x, -2.0, 2.0) * 0.25,
+    "softplus_beta": lambda x: F.softplus(x, beta=3.0) * torch.tanh(x),
+    "hardsigmoid_swish": lambda x: x * F.hardsigmoid(x) + torch.expm1(-x.abs()),
+    "tanhshrink_erfc": lambda x: F.tanhshrink(x) * torch.erfc(0.5 * x).clamp_max(1.5),
+}
+
+
+@pytest.mark.parametrize("name", sorted(FRAMEWORK_CODE))
+def test_framework_functionals_fuse_into_one_kernel_and_match_the_interpreter(name):
+    """Compositions of the framework's own functionals: one fused kernel, value and gradient
+    against the fp64 interpreter run on the program the detector recorded (the programs'
+    meaning is pinned against the framework's fp64 results on the host)."""
+    fn = FRAMEWORK_CODE[name]
+    n = 50_003
+    x = _x(n, 9300 + len(name))
+    gy = inputs.to_storage(inputs.gaussian(n, 1.0, 9400 + len(name)), "f32")
+    x64, gy64 = inputs.storage_to_f64(x), inputs.storage_to_f64(gy)
+    xd = x.to(DEV).requires_grad_(True)
+    with trace.fuse() as t:
+        y = fn(xd)
+        assert isinstance(y, trace.Lazy) and t.kernels == []
+        z = y.reshape(-1)
+    assert len(t.kernels) == 1
+    z.backward(gy.to(DEV))
+    y_ref, d_ref = ochain.eval_chain(t.kernels[0], x64)
+    rel = 2e-6 * np.maximum(1.0, np.abs(x64)) ** 2
+    compare(z.detach(), y_ref, torch.float32, f"traced {name} y", extra_tol=rel * np.maximum(1, np.abs(y_ref)))
+    compare(xd.grad, gy64 * d_ref, torch.float32, f"traced {name} grad",
+            extra_tol=np.abs(gy64) * rel * np.maximum(1, np.abs(d_ref)) * 2 + 2e-6)
+    # and against the framework's own eager result in fp32 (loose: the framework's fp32 error is its own)
+    x_e = x.to(DEV).requires_grad_(True)
+    y_e = fn(x_e)
+    y_e.backward(gy.to(DEV))
+    assert torch.allclose(z.detach(), y_e.detach(), rtol=2e-5, atol=2e-5)
+    assert torch.allclose(xd.grad, x_e.grad, rtol=2e-4, atol=2e-5)

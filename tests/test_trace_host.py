@@ -1,5 +1,6 @@
 """The chain detector's state machine and program builder, on host tensors (recording only:
 nothing is executed, and materialising a chain on the host must fail loudly)."""
+import numpy as np
 import pytest
 import torch
 import torch.nn.functional as F
@@ -96,8 +97,56 @@ def test_unsupported_variants_do_not_start_a_chain():
     x = torch.randn(6)
     xi = torch.arange(6)
     with trace.fuse(require_cuda=False):
-        assert not isinstance(F.softplus(x, beta=2.0), trace.Lazy)
+        assert not isinstance(F.softplus(x, threshold=5.0), trace.Lazy)  # the linear branch would be visible
+        assert not isinstance(F.leaky_relu(x, inplace=True), trace.Lazy)
         assert not isinstance(torch.tanh(xi.double()), trace.Lazy)      # float64 is not a storage type here
         assert not isinstance(x ** 2.5, trace.Lazy)
         assert not isinstance(x + torch.randn(1), trace.Lazy)           # broadcasting a different tensor
         assert isinstance(x ** 2, trace.Lazy)
+
+
+FUNCTIONALS = {
+    "softplus_beta": (lambda t: F.softplus(t, beta=2.5), False),
+    "leaky_relu": (lambda t: F.leaky_relu(t, 0.2), False),
+    "leaky_relu_default": (lambda t: F.leaky_relu(t), False),
+    "selu": (F.selu, False),
+    "celu": (lambda t: F.celu(t, alpha=0.7), False),
+    "hardtanh": (lambda t: F.hardtanh(t, -0.5, 1.5), False),
+    "hardsigmoid": (F.hardsigmoid, False),
+    "logsigmoid": (F.logsigmoid, False),
+    "tanhshrink": (F.tanhshrink, False),
+    "clamp_min": (lambda t: torch.clamp_min(t, -0.25), False),
+    "clamp_max": (lambda t: t.clamp_max(0.75), False),
+    "expm1": (torch.expm1, False),
+    "erfc": (torch.erfc, False),
+    "reciprocal": (torch.reciprocal, True),
+    "rsqrt": (torch.rsqrt, True),
+    "log1p": (torch.log1p, True),
+    "gelu_tanh": (lambda t: F.gelu(t, approximate="tanh"), False),
+    "elu": (lambda t: F.elu(t, alpha=1.3), False),
+    "hardswish": (F.hardswish, False),
+    "relu6": (F.relu6, False),
+}
+
+
+@pytest.mark.parametrize("name", sorted(FUNCTIONALS))
+def test_recorded_program_of_a_functional_means_what_the_framework_computes(name):
+    """The detector's expansion of each functional into primitives, evaluated by the fp64 chain
+    interpreter, against the framework's own fp64 value and autograd gradient."""
+    from oracle import chain
+    fn, positive = FUNCTIONALS[name]
+    g = torch.Generator().manual_seed(11)
+    x32 = torch.randn(4001, generator=g) * 2.5
+    if positive:
+        x32 = x32.abs() + 0.25
+    with trace.fuse(require_cuda=False):
+        lazy = fn(x32)
+        assert isinstance(lazy, trace.Lazy), name
+        program = " ".join(lazy._program)
+    x64 = x32.double().requires_grad_(True)
+    y64 = fn(x64)
+    (d64,) = torch.autograd.grad(y64.sum(), x64)
+    y, d = chain.eval_chain(program, x32.double().numpy())
+    # 1e-7: the framework's own fp64 kernels carry a few fp32 constants (1/6, the softplus threshold)
+    assert np.allclose(y, y64.detach().numpy(), rtol=1e-7, atol=1e-7), (name, program)
+    assert np.allclose(d, d64.numpy(), rtol=1e-7, atol=1e-7), (name, program)
