@@ -10,7 +10,12 @@ input, and the step time, for
   native    : the framework's own fused activation (saves x)
   saveall / recompute / fad : the libnfad kernels behind autograd Functions
 
-Run:  python -m paper_2209_10778_amd.footprint [--dtype bf16] [--batch 32]
+It also reports the paper's own headline quantity, the maximum batch size under a memory
+budget: total peak memory is linear in the batch (weights + a per-sample cost), so it is
+measured at two batch sizes, extrapolated to the budget, and the extrapolated batch is then
+run once to confirm that it fits.
+
+Run:  python -m paper_2209_10778_amd.footprint [--dtype bf16] [--batch 32] [--budget-gib 16]
 Prints one JSON line per (block, activation).
 """
 from __future__ import annotations
@@ -39,6 +44,9 @@ NATIVE = {
     "swish": F.silu,
     "mish": F.mish,
 }
+
+
+REGIMES = ("composite", "native", "saveall", "recompute", "fad")
 
 
 class Act(nn.Module):
@@ -92,34 +100,70 @@ def measure(make_block, x, steps=5):
         block.zero_grad(set_to_none=True)
         x.grad = None
     torch.cuda.synchronize()
-    return held, peak, (time.perf_counter() - t0) / steps * 1e3
+    del block
+    return held, peak, (time.perf_counter() - t0) / max(steps, 1) * 1e3, base + peak
+
+
+def total_peak(make_block, x):
+    """Peak device memory of one forward + backward, everything included (weights, input, grads)."""
+    return measure(make_block, x, steps=0)[3]
+
+
+def max_batch(make_block, make_x, batch, budget_bytes):
+    """Largest batch whose forward + backward fits in budget_bytes: linear model through the
+    peaks measured at batch/2 and batch, then one confirming run at the answer."""
+    lo, hi = max(1, batch // 2), batch
+    p_lo, p_hi = total_peak(make_block, make_x(lo)), total_peak(make_block, make_x(hi))
+    per_sample = (p_hi - p_lo) / (hi - lo)
+    fixed = p_hi - per_sample * hi
+    b = int((budget_bytes - fixed) // per_sample)
+    while b > 1 and total_peak(make_block, make_x(b)) > budget_bytes:    # allocator rounding: step down
+        b -= max(1, b // 200)
+    return b, per_sample
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--dtype", default="bf16", choices=["f32", "f16", "bf16"])
     ap.add_argument("--batch", type=int, default=32)
+    ap.add_argument("--budget-gib", type=float, default=16.0,
+                    help="memory budget of the maximum-batch-size figure (0 = skip it)")
     args = ap.parse_args()
     td = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[args.dtype]
     dev = torch.device("cuda:0")
     torch.manual_seed(1)
+    budget = int(args.budget_gib * 2 ** 30)
     cases = [
         ("bert_base_ffn seq128", lambda k, r: (lambda: bert_ffn(768, k, r)),
-         torch.randn(args.batch * 128, 768, device=dev, dtype=td), ("gelu_tanh", "gelu_erf")),
+         lambda b: torch.randn(b * 128, 768, device=dev, dtype=td), ("gelu_tanh", "gelu_erf")),
         ("resnet50_bottleneck 56x56", lambda k, r: (lambda: resnet_bottleneck(256, 64, k, r)),
-         torch.randn(args.batch, 256, 56, 56, device=dev, dtype=td), ("swish", "mish", "gelu_tanh")),
+         lambda b: torch.randn(b, 256, 56, 56, device=dev, dtype=td), ("swish", "mish", "gelu_tanh")),
     ]
-    for name, maker, x, kinds in cases:
+    for name, maker, make_x, kinds in cases:
+        rows = []
+        x = make_x(args.batch)
         for kind in kinds:
             row = {"block": name, "activation": kind, "dtype": args.dtype, "batch": args.batch, "regimes": {}}
-            for regime in ("composite", "native", "saveall", "recompute", "fad"):
-                held, peak, ms = measure(maker(kind, regime), x)
+            for regime in REGIMES:
+                held, peak, ms, _ = measure(maker(kind, regime), x)
                 row["regimes"][regime] = {"held_after_fwd_MiB": round(held / 2 ** 20, 1),
                                           "peak_MiB": round(peak / 2 ** 20, 1), "ms_per_step": round(ms, 3)}
             r = row["regimes"]
             row["held_composite_over_fad"] = round(r["composite"]["held_after_fwd_MiB"] / r["fad"]["held_after_fwd_MiB"], 3)
             row["held_native_over_fad"] = round(r["native"]["held_after_fwd_MiB"] / r["fad"]["held_after_fwd_MiB"], 3)
             row["time_recompute_over_fad"] = round(r["recompute"]["ms_per_step"] / r["fad"]["ms_per_step"], 3)
+            rows.append(row)
+        del x
+        torch.cuda.empty_cache()
+        for row in rows:
+            if args.budget_gib > 0:          # nothing else resident while the budget is probed
+                mb = {}
+                for regime in REGIMES:
+                    b, per_sample = max_batch(maker(row["activation"], regime), make_x, args.batch, budget)
+                    mb[regime] = {"max_batch": b, "MiB_per_sample": round(per_sample / 2 ** 20, 3)}
+                    torch.cuda.empty_cache()
+                row["max_batch"] = {"budget_GiB": args.budget_gib, **mb,
+                                    "fad_over_composite": round(mb["fad"]["max_batch"] / mb["composite"]["max_batch"], 3)}
             print(json.dumps(row), flush=True)
 
 
