@@ -15,7 +15,7 @@ budget: total peak memory is linear in the batch (weights + a per-sample cost), 
 measured at two batch sizes, extrapolated to the budget, and the extrapolated batch is then
 run once to confirm that it fits.
 
-Run:  python -m paper_2209_10778_amd.footprint [--dtype bf16] [--batch 32] [--budget-gib 16]
+Run:  python -m paper_2209_10778_amd.footprint [--dtype bf16] [--batch 32] [--budget-gib 16] [--whole-models bert|resnet|both]
 Prints one JSON line per (block, activation).
 """
 from __future__ import annotations
@@ -23,6 +23,7 @@ from __future__ import annotations
 import argparse
 import json
 import math
+import sys
 import time
 
 import torch
@@ -73,6 +74,43 @@ def resnet_bottleneck(cin, mid, kind, regime):
         nn.Conv2d(mid, cin, 1, bias=False), nn.BatchNorm2d(cin), Act(kind, regime))
 
 
+class _Bottleneck(nn.Module):
+    def __init__(self, cin, mid, stride, kind, regime):
+        super().__init__()
+        cout = 4 * mid
+        self.body = nn.Sequential(
+            nn.Conv2d(cin, mid, 1, bias=False), nn.BatchNorm2d(mid), Act(kind, regime),
+            nn.Conv2d(mid, mid, 3, stride=stride, padding=1, bias=False), nn.BatchNorm2d(mid), Act(kind, regime),
+            nn.Conv2d(mid, cout, 1, bias=False), nn.BatchNorm2d(cout))
+        self.skip = None if (stride == 1 and cin == cout) else nn.Sequential(
+            nn.Conv2d(cin, cout, 1, stride=stride, bias=False), nn.BatchNorm2d(cout))
+        self.act = Act(kind, regime)
+
+    def forward(self, x):
+        return self.act(self.body(x) + (x if self.skip is None else self.skip(x)))
+
+
+def resnet50(kind, regime):
+    """ResNet-50 (stages of 3, 4, 6, 3 bottlenecks) with every ReLU replaced by the activation,
+    as in the paper's ResNet experiments (Sec. V); random weights."""
+    layers = [nn.Conv2d(3, 64, 7, stride=2, padding=3, bias=False), nn.BatchNorm2d(64), Act(kind, regime),
+              nn.MaxPool2d(3, stride=2, padding=1)]
+    cin = 64
+    for mid, count, stride in ((64, 3, 1), (128, 4, 2), (256, 6, 2), (512, 3, 2)):
+        for i in range(count):
+            layers.append(_Bottleneck(cin, mid, stride if i == 0 else 1, kind, regime))
+            cin = 4 * mid
+    layers += [nn.AdaptiveAvgPool2d(1), nn.Flatten(), nn.Linear(cin, 1000)]
+    return nn.Sequential(*layers)
+
+
+def bert_base_encoder(kind, regime):
+    """Twelve BERT-base encoder layers (hidden 768, 12 heads, FFN 3072, dropout 0.1) without the
+    embeddings; random weights."""
+    return nn.Sequential(*[nn.TransformerEncoderLayer(768, 12, 3072, dropout=0.1, activation=Act(kind, regime),
+                                                      batch_first=True) for _ in range(12)])
+
+
 def measure(make_block, x, steps=5):
     dev = x.device
     torch.manual_seed(0)
@@ -104,9 +142,15 @@ def measure(make_block, x, steps=5):
     return held, peak, (time.perf_counter() - t0) / max(steps, 1) * 1e3, base + peak
 
 
+def _progress(msg):
+    print(f"[footprint] {msg}", file=sys.stderr, flush=True)
+
+
 def total_peak(make_block, x):
     """Peak device memory of one forward + backward, everything included (weights, input, grads)."""
-    return measure(make_block, x, steps=0)[3]
+    p = measure(make_block, x, steps=0)[3]
+    _progress(f"  batch {x.shape[0]}: total peak {p / 2 ** 30:.2f} GiB")
+    return p
 
 
 def max_batch(make_block, make_x, batch, budget_bytes):
@@ -126,6 +170,8 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--dtype", default="bf16", choices=["f32", "f16", "bf16"])
     ap.add_argument("--batch", type=int, default=32)
+    ap.add_argument("--whole-models", choices=("bert", "resnet", "both"), default=None,
+                    help="BERT-base encoder (12 layers) and/or ResNet-50 instead of single blocks")
     ap.add_argument("--budget-gib", type=float, default=16.0,
                     help="memory budget of the maximum-batch-size figure (0 = skip it)")
     args = ap.parse_args()
@@ -139,6 +185,13 @@ def main():
         ("resnet50_bottleneck 56x56", lambda k, r: (lambda: resnet_bottleneck(256, 64, k, r)),
          lambda b: torch.randn(b, 256, 56, 56, device=dev, dtype=td), ("swish", "mish", "gelu_tanh")),
     ]
+    if args.whole_models:
+        cases = [c for c in [
+            ("bert_base_encoder 12 layers seq128", lambda k, r: (lambda: bert_base_encoder(k, r)),
+             lambda b: torch.randn(b, 128, 768, device=dev, dtype=td), ("gelu_tanh", "gelu_erf")),
+            ("resnet50 224x224", lambda k, r: (lambda: resnet50(k, r)),
+             lambda b: torch.randn(b, 3, 224, 224, device=dev, dtype=td), ("swish", "mish", "gelu_tanh")),
+        ] if args.whole_models == "both" or c[0].startswith(args.whole_models)]
     for name, maker, make_x, kinds in cases:
         rows = []
         x = make_x(args.batch)
@@ -146,6 +199,7 @@ def main():
             row = {"block": name, "activation": kind, "dtype": args.dtype, "batch": args.batch, "regimes": {}}
             for regime in REGIMES:
                 held, peak, ms, _ = measure(maker(kind, regime), x)
+                _progress(f"{name} {kind} {regime}: batch {args.batch} measured, {ms:.2f} ms/step")
                 row["regimes"][regime] = {"held_after_fwd_MiB": round(held / 2 ** 20, 1),
                                           "peak_MiB": round(peak / 2 ** 20, 1), "ms_per_step": round(ms, 3)}
             r = row["regimes"]
@@ -160,6 +214,7 @@ def main():
                 mb = {}
                 for regime in REGIMES:
                     b, per_sample = max_batch(maker(row["activation"], regime), make_x, args.batch, budget)
+                    _progress(f"{name} {row['activation']} {regime}: max batch {b}")
                     mb[regime] = {"max_batch": b, "MiB_per_sample": round(per_sample / 2 ** 20, 3)}
                     torch.cuda.empty_cache()
                 row["max_batch"] = {"budget_GiB": args.budget_gib, **mb,
