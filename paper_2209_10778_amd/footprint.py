@@ -9,6 +9,8 @@ input, and the step time, for
               every primitive saves what its own backward needs)
   native    : the framework's own fused activation (saves x)
   saveall / recompute / fad : the libnfad kernels behind autograd Functions
+  traced    : the composite code again, unchanged, but run under the chain detector
+              (trace.fuse), which finds the chains and fuses them by itself
 
 It also reports the paper's own headline quantity, the maximum batch size under a memory
 budget: total peak memory is linear in the batch (weights + a per-sample cost), so it is
@@ -31,6 +33,7 @@ import torch.nn as nn
 import torch.nn.functional as F
 
 from . import autograd as A
+from . import trace
 
 _C = math.sqrt(2.0 / math.pi)
 COMPOSITE = {
@@ -47,7 +50,7 @@ NATIVE = {
 }
 
 
-REGIMES = ("composite", "native", "saveall", "recompute", "fad")
+REGIMES = ("composite", "native", "saveall", "recompute", "fad", "traced")
 
 
 class Act(nn.Module):
@@ -56,7 +59,7 @@ class Act(nn.Module):
         self.kind, self.regime = kind, regime
 
     def forward(self, x):
-        if self.regime == "composite":
+        if self.regime in ("composite", "traced"):
             return COMPOSITE[self.kind](x)
         if self.regime == "native":
             return NATIVE[self.kind](x)
@@ -111,10 +114,25 @@ def bert_base_encoder(kind, regime):
                                                       batch_first=True) for _ in range(12)])
 
 
+class Traced(nn.Module):
+    """The model as the user wrote it (composite activations), run under the chain detector."""
+
+    def __init__(self, inner):
+        super().__init__()
+        self.inner = inner
+
+    def forward(self, x):
+        with trace.fuse():
+            y = self.inner(x)
+        return y.materialize() if isinstance(y, trace.Lazy) else y
+
+
 def measure(make_block, x, steps=5):
     dev = x.device
     torch.manual_seed(0)
     block = make_block().to(device=dev, dtype=x.dtype)
+    if any(isinstance(m, Act) and m.regime == "traced" for m in block.modules()):
+        block = Traced(block)
     x = x.clone().requires_grad_(True)
     for _ in range(2):                                   # warm up allocator, autotuners
         block(x).float().square().mean().backward()

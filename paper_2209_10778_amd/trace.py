@@ -20,6 +20,12 @@ A binary operator is fad only if both operands derive from the same source tenso
 of them is a Python number (Sec. III-A); otherwise it is an nfad operator and ends the chain.
 A lazy tensor used by several consumers is materialised once per distinct chain (M outputs).
 
+A chain of ONE plain primitive (NY directly followed by YN; Sec. IV-B "Efficiency" treats this
+case specially too) is not fused: the primitive runs natively, because its own backward keeps
+at most its input or its output, both alive anyway, or nothing at all (x * c), whereas a
+fused kernel would add a saved tangent.  Single calls of the framework's fused activations
+(silu, gelu, mish, ...) ARE replaced: same memory, and the backward becomes one multiply.
+
     from paper_2209_10778_amd import trace
     with trace.fuse() as t:
         y = x * torch.tanh(torch.nn.functional.softplus(x))     # user-written Mish
@@ -49,17 +55,25 @@ class Lazy(torch.Tensor):
     """A fad tensor: the not-yet-executed chain `program` applied to `source`."""
 
     @staticmethod
-    def __new__(cls, source: torch.Tensor, program: List[str], tracer: "fuse"):
+    def __new__(cls, source: torch.Tensor, program: List[str], tracer: "fuse", nops: int = 2, native=None):
         r = torch.Tensor._make_wrapper_subclass(cls, source.shape, dtype=source.dtype, device=source.device,
                                                 requires_grad=source.requires_grad)
         r._source, r._program, r._tracer, r._value = source, list(program), tracer, None
+        r._nops, r._native = nops, native      # operators recorded; (func, args, kwargs) of a lone primitive
         return r
 
     def materialize(self) -> torch.Tensor:
-        """YN: run the fused forward kernel of the recorded chain; keeps only dydx for backward."""
+        """YN: run the fused forward kernel of the recorded chain; keeps only dydx for backward.
+        A chain of one plain primitive runs that primitive natively instead."""
         if self._value is None:
-            self._value = A.chain(self._source, " ".join(self._program))
-            self._tracer.kernels.append(" ".join(self._program))
+            if self._nops == 1 and self._native is not None:
+                func, args, kwargs = self._native
+                self._value = func(*args, **kwargs)
+                self._tracer.native_singles += 1
+            else:
+                self._value = A.chain(self._source, " ".join(self._program))
+                self._tracer.kernels.append(" ".join(self._program))
+            self._native = None
         return self._value
 
     def __repr__(self):
@@ -127,6 +141,10 @@ _UNARY = {
     + ["*"] + a + ["*", "*", "+", "*", "tanh", "+", "*"],
 }
 _BINARY = {"add": _bin("+"), "sub": _bin("-"), "mul": _bin("*"), "div": _bin("/")}
+# Activations the framework runs as one fused operator that keeps its input: replacing a single
+# call by the fused forward-AD kernel costs no memory and makes the backward one multiply.
+_FUSED_FUNCTIONALS = {"silu", "mish", "gelu", "elu", "selu", "celu", "hardswish", "hardsigmoid", "softsign",
+                      "logsigmoid", "tanhshrink", "softplus", "leaky_relu"}
 
 
 def _op_name(func):
@@ -156,6 +174,7 @@ class fuse(TorchFunctionMode):
         self.require_cuda = require_cuda   # False only lets chains be RECORDED on host tensors (tests)
         self.states: List[str] = []      # forward state of every tensor-operator pair seen
         self.kernels: List[str] = []     # chain programs that were materialised, in order
+        self.native_singles = 0          # one-primitive chains that were run natively instead
 
     # ---- operand analysis
     def _operand(self, a, source):
@@ -268,7 +287,9 @@ class fuse(TorchFunctionMode):
                     prog = _BINARY[base](a, b)
         if prog is None or "x" not in prog or len(prog) > 250:
             return None
-        return Lazy(source, prog, self)
+        nops = 1 + sum(a._nops for a in lazies)
+        native = (func, args, dict(kwargs)) if not lazies and op not in _FUSED_FUNCTIONALS else None
+        return Lazy(source, prog, self, nops, native)
 
     # ---- the state machine
     def _dispatch(self, func, args, kwargs):

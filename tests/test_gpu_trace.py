@@ -88,11 +88,15 @@ def test_mixing_sources_ends_both_chains():
     x = _x(5_000, 9400).to(DEV)
     w = _x(5_000, 9401).to(DEV)
     with trace.fuse() as t:
-        y = torch.tanh(x) * torch.sigmoid(w)     # operands from different sources: nfad operator
+        y = torch.tanh(x * 0.5) * torch.sigmoid(-w)     # operands from different sources: nfad operator
     assert not isinstance(y, trace.Lazy)
-    assert sorted(t.kernels) == ["x sigmoid", "x tanh"]
-    ref = np.tanh(inputs.storage_to_f64(x.cpu())) * (1 / (1 + np.exp(-inputs.storage_to_f64(w.cpu()))))
+    assert sorted(t.kernels) == ["x 0.5 * tanh", "x neg sigmoid"]
+    ref = np.tanh(0.5 * inputs.storage_to_f64(x.cpu())) * (1 / (1 + np.exp(inputs.storage_to_f64(w.cpu()))))
     compare(y, ref, torch.float32, "mixed sources", extra_tol=1e-6)
+    with trace.fuse() as t:                             # each side a lone primitive: both run natively
+        y = torch.tanh(x) * torch.sigmoid(w)
+    assert t.kernels == [] and t.native_singles == 2
+    assert torch.equal(y, torch.tanh(x) * torch.sigmoid(w))
 
 
 def test_a_small_network_with_user_written_mish_trains_a_step():
@@ -106,7 +110,8 @@ def test_a_small_network_with_user_written_mish_trains_a_step():
 
     with trace.fuse() as t:
         net(x).square().mean().backward()
-    assert t.kernels == ["x x softplus tanh *", "x x *"]      # the activation, and the loss's square
+    assert t.kernels == ["x x softplus tanh *"]     # the activation; the loss's lone square runs natively
+    assert t.native_singles == 1
     g1 = [p.grad.clone() for p in list(lin1.parameters()) + list(lin2.parameters())]
     for p in list(lin1.parameters()) + list(lin2.parameters()):
         p.grad = None
@@ -154,3 +159,32 @@ def test_framework_functionals_fuse_into_one_kernel_and_match_the_interpreter(na
     y_e.backward(gy.to(DEV))
     assert torch.allclose(z.detach(), y_e.detach(), rtol=2e-5, atol=2e-5)
     assert torch.allclose(xd.grad, x_e.grad, rtol=2e-4, atol=2e-5)
+
+
+def test_whole_layers_under_the_detector_match_eager_and_fuse_only_the_activations():
+    """A transformer encoder layer and a ResNet bottleneck written with composite activations,
+    run unchanged under the detector: same result and gradients as eager execution, one fused
+    kernel per activation call, lone primitives elsewhere in the layer (q * scale, ...) left native."""
+    from paper_2209_10778_amd import footprint as fp
+    torch.manual_seed(3)
+    enc = torch.nn.TransformerEncoderLayer(64, 4, 128, dropout=0.0, activation=fp.Act("gelu_tanh", "composite"),
+                                           batch_first=True).to(DEV)
+    res = fp.resnet_bottleneck(16, 8, "mish", "composite").to(DEV)
+    for model, x, n_act in ((enc, torch.randn(5, 12, 64, device=DEV), 1), (res, torch.randn(3, 16, 10, 10, device=DEV), 3)):
+        xe = x.clone().requires_grad_(True)
+        ye = model(xe)
+        ye.square().mean().backward()
+        ge = [p.grad.clone() for p in model.parameters()]
+        model.zero_grad(set_to_none=True)
+        xt = x.clone().requires_grad_(True)
+        with trace.fuse() as t:
+            yt = model(xt)
+        if isinstance(yt, trace.Lazy):
+            yt = yt.materialize()
+        yt.square().mean().backward()
+        assert len(t.kernels) == n_act, t.kernels
+        assert torch.allclose(yt, ye, rtol=1e-4, atol=1e-5)
+        assert torch.allclose(xt.grad, xe.grad, rtol=1e-3, atol=1e-6)
+        for p, g in zip(model.parameters(), ge):
+            assert torch.allclose(p.grad, g, rtol=1e-3, atol=1e-5)
+        model.zero_grad(set_to_none=True)

@@ -80,9 +80,30 @@ def test_binary_operator_needs_the_same_source():
         a = torch.tanh(x)                 # NY
         b = torch.sigmoid(w)              # NY (another chain, another source)
         assert isinstance(a, trace.Lazy) and isinstance(b, trace.Lazy) and a._source is x and b._source is w
-        with pytest.raises((ValueError, RuntimeError, ImportError)):
-            a * b                         # different sources: nfad operator, YN; materialising on the host fails
+        c = a * b                         # different sources: nfad operator, YN for both chains
     assert active(t.states)[:3] == ["NY", "NY", "YN"]
+    # each chain is ONE plain primitive: run natively, nothing fused (Sec. IV-B "Efficiency")
+    assert t.kernels == [] and t.native_singles == 2 and not isinstance(c, trace.Lazy)
+    assert torch.equal(c, torch.tanh(x) * torch.sigmoid(w))
+
+
+def test_a_longer_chain_on_the_host_has_no_fallback():
+    x = torch.randn(4, 4)
+    with trace.fuse(require_cuda=False):
+        a = torch.tanh(x) * x             # two operators: a real chain
+        with pytest.raises((ValueError, RuntimeError, ImportError)):
+            a.sum()                       # materialising needs the GPU library: no CPU fallback
+
+
+def test_single_operator_rule():
+    x = torch.randn(16)
+    with trace.fuse(require_cuda=False) as t:
+        assert torch.equal((x * 0.125).sum(), (x * 0.125).sum())          # lone x * c: native
+        assert t.native_singles == 2 and t.kernels == []
+        lone = F.silu(x)                                                  # a fused functional: replaced
+        assert isinstance(lone, trace.Lazy) and lone._nops == 1 and lone._native is None
+        two = torch.exp(-x)
+        assert two._nops == 2 and two._native is None
 
 
 def test_non_fad_operator_is_passed_through_untouched():
