@@ -40,6 +40,8 @@ def parse_args():
                          "known-size kernel that rocprofv3 FETCH_SIZE/WRITE_SIZE readings are scaled by")
     ap.add_argument("--prewarm-s", type=float, default=0.25,
                     help="seconds of untimed steps before the warm-up steps (reaches steady clocks)")
+    ap.add_argument("--kernel-rounds", type=int, default=3,
+                    help="rounds over the list of kernels; the median round of each kernel is reported")
     ap.add_argument("--kernel-warm-s", type=float, default=0.3,
                     help="seconds of untimed launches of a kernel before its launch duration is measured: the "
                          "duration keeps settling (by 2-4 %%) for a few hundred ms after the kernel mix changes")
@@ -152,27 +154,35 @@ def main():
     # a different kernel mix reads 2-4 % slower than in steady state), so each kernel first runs
     # alone for kernel_warm_s; the last warm-up launches are queued right in front of the timed
     # region (no idle gap).
-    def time_launches(fn):
-        timed = runner([fn], args.steps)
-        e0 = torch.cuda.Event(enable_timing=True)
-        e1 = torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        t_w = time.perf_counter()
-        while time.perf_counter() - t_w < args.kernel_warm_s:   # sustained launches of THIS kernel
-            for _ in range(4):
-                timed()
-            torch.cuda.synchronize()
-        for _ in range(-(-max(300, args.warmup) // args.steps)):
-            timed()
-        e0.record(stream)
-        timed()
-        e1.record(stream)
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) * 1e3 / args.steps
+    def time_kernels(fns):
+        """{name: launch duration in us}: every kernel is measured in `--kernel-rounds` rounds over the
+        whole list and the median round is reported, so that no kernel owes its figure to its
+        place in the process (the first seconds of a process read 1-3 % slow on some parts)."""
+        timed = {name: runner([fn], args.steps) for name, fn in fns.items()}
+        samples = {name: [] for name in fns}
+        for _ in range(max(1, args.kernel_rounds)):
+            for name, run in timed.items():
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                torch.cuda.synchronize()
+                t_w = time.perf_counter()
+                while time.perf_counter() - t_w < args.kernel_warm_s:   # sustained launches of THIS kernel
+                    for _ in range(4):
+                        run()
+                    torch.cuda.synchronize()
+                for _ in range(-(-max(300, args.warmup) // args.steps)):
+                    run()
+                e0.record(stream)
+                run()
+                e1.record(stream)
+                torch.cuda.synchronize()
+                samples[name].append(e0.elapsed_time(e1) * 1e3 / args.steps)
+        return {name: sorted(v)[len(v) // 2] for name, v in samples.items()}
 
     per_kernel = {}
+    launch_us = time_kernels({name: fn for name, (fn, _) in kernels.items()})
     for name, (fn, words) in kernels.items():
-        us = time_launches(fn)
+        us = launch_us[name]
         gbps = words * n * es / (us * 1e-6) / 1e9
         per_kernel[name] = {"us": round(us, 2), "bytes_per_elem": words * es, "GB/s": round(gbps, 1),
                             "frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4),
@@ -203,10 +213,12 @@ def main():
         t_c = time.perf_counter()
         jit_id = nfad.nfad_chain_compile("x x softplus tanh *")    # Mish again, compiled at run time
         jit_compile_s = time.perf_counter() - t_c
-        for cid in list(range(nfad.nfad_chain_count())) + [jit_id]:
-            us = time_launches(lambda s, st, cid=cid: nfad.nfad_chain_fwd(cid, s["x"], s["y"], s["dydx"], st))
+        ids = list(range(nfad.nfad_chain_count())) + [jit_id]
+        label = lambda cid: nfad.nfad_chain_name(cid) if cid != jit_id else "runtime-compiled mish"
+        chain_us = time_kernels({label(cid): (lambda s, st, cid=cid: nfad.nfad_chain_fwd(cid, s["x"], s["y"], s["dydx"], st))
+                                 for cid in ids})
+        for key, us in chain_us.items():
             gbps = 3 * n * es / (us * 1e-6) / 1e9
-            key = nfad.nfad_chain_name(cid) if cid != jit_id else "runtime-compiled mish"
             chains[key] = {"us": round(us, 2), "GB/s": round(gbps, 1),
                            "frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4)}
         chains["runtime-compiled mish"]["compile_s"] = round(jit_compile_s, 2)
