@@ -186,15 +186,31 @@ __device__ __forceinline__ Dual softplus_(Dual a) {  // ln(1 + e^v) = max(v, 0) 
   const float r = rcp(1.0f + e);
   return Dual{__builtin_fmaxf(a.v, 0.0f) + l1p, (a.v > 0.0f ? r : e * r) * a.d};
 }
+template <bool kWide>
+__device__ __forceinline__ float erfc_abs_(float v, float& E) {  // erfc(|v|), and E = exp(-v^2)
+  const float s = 1.41421356237309504880f * __builtin_fabsf(v);
+  E = ex2((-0.5f * kLog2e) * (s * s));
+  if constexpr (kWide) return 2.0f * half_erfcx<ErfcxWide>(s) * E;
+  else return 2.0f * half_erfcx<ErfcxNarrow>(s) * E;
+}
+template <bool kWide>
 __device__ __forceinline__ Dual erf_(Dual a) {  // erf' = 2/sqrt(pi) exp(-v^2)
-  const float s = 1.41421356237309504880f * __builtin_fabsf(a.v);
-  const float E = ex2((-0.5f * kLog2e) * (s * s));  // exp(-v^2)
-  const float erfc_a = 2.0f * half_erfcx<ErfcxWide>(s) * E;
+  float E;
+  const float erfc_a = erfc_abs_<kWide>(a.v, E);
   // small |v|: 1 - erfc cancels; use the series 2/sqrt(pi) (v - v^3/3 + v^5/10)
   const float v2 = a.v * a.v;
   const float series = 1.12837916709551257390f * a.v * fma_(v2, fma_(v2, 0.1f, -0.33333333f), 1.0f);
   const float big = __builtin_copysignf(1.0f - erfc_a, a.v);
   return Dual{__builtin_fabsf(a.v) < 0.125f ? series : big, (1.12837916709551257390f * E) * a.d};
+}
+// 1 + erf(v) = erfc(-v) in one step: erfc(|v|) on the negative side, 2 - erfc(|v|) on the positive
+// one.  No cancellation anywhere (1 + erf(v) computed literally loses everything below v ~ -4),
+// so neither the small-argument series of erf nor its select is needed.
+template <bool kWide>
+__device__ __forceinline__ Dual one_plus_erf_(Dual a) {
+  float E;
+  const float erfc_a = erfc_abs_<kWide>(a.v, E);
+  return Dual{a.v < 0.0f ? erfc_a : 2.0f - erfc_a, (1.12837916709551257390f * E) * a.d};
 }
 // tanh(softplus(v)) in one step: with e = exp(v) and n = e (e + 2) it is n / (n + 2), and its
 // derivative is 4 e (e + 1) / (n + 2)^2: one exponential and one reciprocal instead of two
@@ -227,10 +243,22 @@ NFAD_CHAIN_UNARY(Log, log_);
 NFAD_CHAIN_UNARY(Sigmoid, sigmoid_);
 NFAD_CHAIN_UNARY(Tanh, tanh_<kWide>);
 NFAD_CHAIN_UNARY(Softplus, softplus_<kWide>);
-NFAD_CHAIN_UNARY(Erf, erf_);
+NFAD_CHAIN_UNARY(Erf, erf_<kWide>);
 #undef NFAD_CHAIN_UNARY
 
-// Fused pair (the composer's one peephole): tanh directly on a softplus, the core of Mish.
+// Fused pairs (the composer's two peepholes): 1 + erf, the core of GELU as usually written ...
+template <class C, class A>
+struct Add<Const<C>, Erf<A>> {
+  template <bool kWide>
+  __device__ __forceinline__ static Dual eval(Dual x) {
+    const Dual a = to_dual(A::template eval<kWide>(x));
+    if constexpr (C::value == 1.0f) return one_plus_erf_<kWide>(a);
+    else return add_(Konst{C::value}, erf_<kWide>(a));
+  }
+};
+template <class A, class C>
+struct Add<Erf<A>, Const<C>> : Add<Const<C>, Erf<A>> {};
+// ... and tanh directly on a softplus, the core of Mish.
 template <class A>
 struct Tanh<Softplus<A>> {
   template <bool kWide>
