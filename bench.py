@@ -224,6 +224,34 @@ def main():
         chains["runtime-compiled mish"]["compile_s"] = round(jit_compile_s, 2)
         nfad.nfad_chain_release(jit_id)
 
+        # one source, two outputs (R^1 -> R^2): the fused multi-output forward and the merged backward
+        # against the same work done chain by chain
+        progs = ["x tanh x *", "x tanh sigmoid"]
+        mid = nfad.nfad_chain_compile_multi(progs)
+        sids = [nfad.nfad_chain_compile(p) for p in progs]
+        for s in sets:
+            s["y2"], s["d2"] = torch.empty_like(s["y"]), torch.empty_like(s["dydx"])
+
+        def fwd_separate(s, st):
+            nfad.nfad_chain_fwd(sids[0], s["x"], s["y"], s["dydx"], st)
+            nfad.nfad_chain_fwd(sids[1], s["x"], s["y2"], s["d2"], st)
+
+        multi_us = time_kernels({
+            "fwd_multi": lambda s, st: nfad.nfad_chain_fwd_multi(mid, s["x"], [s["y"], s["y2"]], [s["dydx"], s["d2"]], st),
+            "fwd_separate": fwd_separate,
+            "bwd_multi": lambda s, st: nfad.nfad_bwd_multi([s["gy"], s["y"]], [s["dydx"], s["d2"]], s["gx"], st),
+        })
+        chains["two_outputs"] = {
+            "programs": progs,
+            "fwd_multi": {"us": round(multi_us["fwd_multi"], 2), "bytes_per_elem": 5 * es,
+                          "GB/s": round(5 * n * es / (multi_us["fwd_multi"] * 1e-6) / 1e9, 1)},
+            "fwd_chain_by_chain": {"us": round(multi_us["fwd_separate"], 2), "bytes_per_elem": 6 * es},
+            "bwd_multi": {"us": round(multi_us["bwd_multi"], 2), "bytes_per_elem": 5 * es,
+                          "GB/s": round(5 * n * es / (multi_us["bwd_multi"] * 1e-6) / 1e9, 1)},
+        }
+        for cid in [mid] + sids:
+            nfad.nfad_chain_release(cid)
+
     fwd = per_kernel["nfad_fwd"]
     roofline = {"kernel": "nfad_fwd", "bound": "hbm", "achieved": fwd["GB/s"], "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(fwd["GB/s"] / HBM_PEAK_GBPS, 4), "traffic": None,

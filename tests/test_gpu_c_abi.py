@@ -1,7 +1,7 @@
 """The C ABI from a plain C99 program (tests/c_abi/nfad_c_check.c): no Python and no PyTorch
 between the caller and libnfad.  The program allocates with the HIP runtime's C API, calls all
 six passes for the four activations plus a run-time compiled chain, and checks the results
-against the fp64 oracle it links; this test only runs it and reads its verdict."""
+against the fp64 oracle it links; this test only runs it and reads its exit status."""
 import os
 import subprocess
 
