@@ -147,23 +147,24 @@ _FUSED_FUNCTIONALS = {"silu", "mish", "gelu", "elu", "selu", "celu", "hardswish"
                       "logsigmoid", "tanhshrink", "softplus", "leaky_relu"}
 
 
+_OP_TABLE = {
+    "add": "add", "__add__": "add", "__radd__": "radd", "sub": "sub", "__sub__": "sub", "__rsub__": "rsub",
+    "rsub": "rsub", "mul": "mul", "__mul__": "mul", "__rmul__": "rmul", "multiply": "mul",
+    "div": "div", "true_divide": "div", "__truediv__": "div", "__rtruediv__": "rdiv", "__rdiv__": "rdiv", "__div__": "div", "divide": "div",
+    "neg": "neg", "negative": "neg", "__neg__": "neg", "exp": "exp", "log": "log", "tanh": "tanh",
+    "sigmoid": "sigmoid", "softplus": "softplus", "erf": "erf", "square": "square", "silu": "silu",
+    "mish": "mish", "gelu": "gelu", "pow": "pow", "__pow__": "pow", "relu": "relu", "abs": "abs",
+    "absolute": "abs", "__abs__": "abs", "sqrt": "sqrt", "relu6": "relu6", "hardswish": "hardswish",
+    "softsign": "softsign", "elu": "elu", "clamp": "clamp", "clip": "clamp",
+    "logsigmoid": "logsigmoid", "log_sigmoid": "logsigmoid", "tanhshrink": "tanhshrink", "hardsigmoid": "hardsigmoid",
+    "reciprocal": "reciprocal", "rsqrt": "rsqrt", "expm1": "expm1", "log1p": "log1p", "erfc": "erfc",
+    "selu": "selu", "leaky_relu": "leaky_relu", "celu": "celu", "hardtanh": "hardtanh",
+    "clamp_min": "clamp_min", "clamp_max": "clamp_max",
+}
+
+
 def _op_name(func):
-    n = getattr(func, "__name__", "")
-    table = {
-        "add": "add", "__add__": "add", "__radd__": "radd", "sub": "sub", "__sub__": "sub", "__rsub__": "rsub",
-        "rsub": "rsub", "mul": "mul", "__mul__": "mul", "__rmul__": "rmul", "multiply": "mul",
-        "div": "div", "true_divide": "div", "__truediv__": "div", "__rtruediv__": "rdiv", "__rdiv__": "rdiv", "__div__": "div", "divide": "div",
-        "neg": "neg", "negative": "neg", "__neg__": "neg", "exp": "exp", "log": "log", "tanh": "tanh",
-        "sigmoid": "sigmoid", "softplus": "softplus", "erf": "erf", "square": "square", "silu": "silu",
-        "mish": "mish", "gelu": "gelu", "pow": "pow", "__pow__": "pow", "relu": "relu", "abs": "abs",
-        "absolute": "abs", "__abs__": "abs", "sqrt": "sqrt", "relu6": "relu6", "hardswish": "hardswish",
-        "softsign": "softsign", "elu": "elu", "clamp": "clamp", "clip": "clamp",
-        "logsigmoid": "logsigmoid", "log_sigmoid": "logsigmoid", "tanhshrink": "tanhshrink", "hardsigmoid": "hardsigmoid",
-        "reciprocal": "reciprocal", "rsqrt": "rsqrt", "expm1": "expm1", "log1p": "log1p", "erfc": "erfc",
-        "selu": "selu", "leaky_relu": "leaky_relu", "celu": "celu", "hardtanh": "hardtanh",
-        "clamp_min": "clamp_min", "clamp_max": "clamp_max",
-    }
-    return table.get(n)
+    return _OP_TABLE.get(getattr(func, "__name__", ""))
 
 
 class fuse(TorchFunctionMode):
@@ -315,7 +316,14 @@ class fuse(TorchFunctionMode):
         return func(*args, **kwargs)               # NN (or the operator after YN)
 
     def __torch_function__(self, func, types, args=(), kwargs=None):
-        return self._dispatch(func, args, kwargs or {})
+        kwargs = kwargs or {}
+        # Fast path for the bulk of a model's operators: not a fad operator and no lazy operand in
+        # sight -> ordinary execution (NN), not logged.  A lazy tensor nested deeper in the arguments
+        # is still caught: the call below then reaches Lazy.__torch_function__.
+        if getattr(func, "__name__", "") not in _OP_TABLE and not any(type(a) is Lazy for a in args) \
+                and not any(type(v) is Lazy for v in kwargs.values()):
+            return func(*args, **kwargs)
+        return self._dispatch(func, args, kwargs)
 
 
 # attribute reads and bookkeeping calls that are not operators of the graph
