@@ -12,6 +12,8 @@ backward, `mode="saveall"` keeps every intermediate of ordinary back-propagation
 """
 from __future__ import annotations
 
+import collections
+
 import torch
 
 from . import binding as B
@@ -142,21 +144,38 @@ class _FadChainMulti(torch.autograd.Function):
 def chain_multi(x: torch.Tensor, programs):
     """Several chains over the same source, fused into one forward kernel (R^1 -> R^M)."""
     key = tuple(programs)
-    if key not in _compiled:
-        _compiled[key] = B.nfad_chain_compile_multi(list(programs))
-    return _FadChainMulti.apply(x, _compiled[key], len(programs))
+    cid = _remember(key, lambda: B.nfad_chain_compile_multi(list(programs)))
+    return _FadChainMulti.apply(x, cid, len(programs))
 
 
-_compiled: dict = {}
+# program (or tuple of programs) -> chain id, least recently used first.  Bounded: code that bakes a
+# changing number into its chains (x * step_size) would otherwise compile, and keep, a kernel per value.
+_compiled: "collections.OrderedDict" = collections.OrderedDict()
+MAX_COMPILED = 512
+
+
+def _remember(key, make) -> int:
+    if key in _compiled:
+        _compiled.move_to_end(key)
+        return _compiled[key]
+    cid = make()
+    _compiled[key] = cid
+    while len(_compiled) > MAX_COMPILED:
+        _, old = _compiled.popitem(last=False)
+        if old >= B.NFAD_CHAIN_JIT_BASE:           # built-in chains are not ours to release
+            torch.cuda.synchronize()               # no launch of the evicted kernel may be in flight
+            B.nfad_chain_release(old)
+    return cid
 
 
 def _chain_id(chain) -> int:
     if isinstance(chain, int):
         return chain
-    if chain not in _compiled:
+
+    def make():
         names = {B.nfad_chain_name(i): i for i in range(B.nfad_chain_count())}
-        _compiled[chain] = names[chain] if chain in names else B.nfad_chain_compile(chain)
-    return _compiled[chain]
+        return names[chain] if chain in names else B.nfad_chain_compile(chain)
+    return _remember(chain, make)
 
 
 def gelu(x, approximate: str = "none", mode: str = "fad"):

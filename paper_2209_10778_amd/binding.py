@@ -10,6 +10,7 @@ GELU_TANH, GELU_ERF, SWISH, MISH = 0, 1, 2, 3
 KINDS = (GELU_TANH, GELU_ERF, SWISH, MISH)
 KIND_NAMES = {GELU_TANH: "gelu_tanh", GELU_ERF: "gelu_erf", SWISH: "swish", MISH: "mish"}
 F32, F16, BF16 = 0, 1, 2
+NFAD_CHAIN_JIT_BASE = 1000   # ids of run-time compiled chains start here (include/nfad.h)
 _DTYPE_CODE = {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}
 
 _HERE = os.path.dirname(os.path.abspath(__file__))

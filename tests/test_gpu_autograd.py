@@ -97,3 +97,24 @@ def test_non_contiguous_and_16bit_inputs(dtype):
     # two roundings (dydx, then the product), scaled by |gy|
     tol = np.abs(gy64) * tolerance(torch.from_numpy(d_ref), td).numpy()
     compare(xd.grad.contiguous(), g_ref, td, f"non-contiguous grad {dtype}", extra_tol=tol)
+
+
+def test_compiled_chain_cache_is_bounded(monkeypatch):
+    """Chains that bake in a changing constant must not accumulate kernels without limit: the
+    front end keeps the most recently used programs and releases the rest."""
+    import paper_2209_10778_amd as nfad
+    import collections
+    monkeypatch.setattr(A, "_compiled", collections.OrderedDict())     # a fresh table for this test
+    monkeypatch.setattr(A, "MAX_COMPILED", 3)
+    x = torch.randn(1000, device=DEV)
+    ids = []
+    for k in range(6):
+        prog = f"x {1.5 + k} * tanh x *"
+        y = A.chain(x, prog)
+        ids.append(A._compiled[prog])
+        assert torch.allclose(y, torch.tanh(x * (1.5 + k)) * x, rtol=1e-5, atol=1e-6)
+    assert len(A._compiled) <= A.MAX_COMPILED
+    assert all(nfad.nfad_chain_name(i) is None for i in ids[:3])        # evicted and released
+    assert all(nfad.nfad_chain_name(i) is not None for i in ids[3:])    # still live
+    y = A.chain(x, "x 1.5 * tanh x *")                                  # an evicted program compiles again
+    assert torch.allclose(y, torch.tanh(x * 1.5) * x, rtol=1e-5, atol=1e-6)
