@@ -210,3 +210,29 @@ def test_random_programs_match_interpreter():
             compare(y, y_ref, td, f"random {prog!r} y {dtype}", extra_tol=rel * np.maximum(1.0, np.abs(y_ref)))
             compare(d, d_ref, td, f"random {prog!r} dydx {dtype}", extra_tol=rel * np.maximum(1.0, np.abs(d_ref)))
         nfad.nfad_chain_release(cid)
+
+
+# ------------------------------------------------------------------ exhaustive 16-bit inputs
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_every_16bit_pattern_through_every_builtin_chain(dtype):
+    """All finite fp16 / bf16 bit patterns within the range where the chain as spelled is finite
+    (the same limits as the random-input test), through every built-in chain."""
+    td = DTYPES[dtype]
+    bits = torch.arange(65536, dtype=torch.int32).to(torch.int16)
+    x_all = bits.view(td)
+    xf = x_all.to(torch.float64)
+    report = {}
+    for cid, name in chains():
+        lim = {"exp": 10.0, "swish_table1": 60.0}.get(name, 100.0)
+        x = x_all[torch.isfinite(xf) & (xf.abs() <= lim)].contiguous()
+        x64 = inputs.storage_to_f64(x)
+        y_ref, d_ref = chain.eval_chain(nfad.nfad_chain_program(cid), x64)
+        xd = x.to(DEV)
+        y = torch.full_like(xd, float("nan"))
+        d = torch.full_like(xd, float("nan"))
+        nfad.nfad_chain_fwd(cid, xd, y, d)
+        rel = 2e-6 * np.maximum(1.0, np.abs(x64))
+        sy = compare(y, y_ref, td, f"exhaustive chain {name} y {dtype}", extra_tol=rel * np.maximum(1.0, np.abs(y_ref)))
+        sd = compare(d, d_ref, td, f"exhaustive chain {name} dydx {dtype}", extra_tol=rel * np.maximum(1.0, np.abs(d_ref)))
+        report[name] = (round(sy["max_ulp"], 2), round(sd["max_ulp"], 2))
+    print(f"\n[exhaustive chains {dtype}] max ulp (y, dydx): {report}")
