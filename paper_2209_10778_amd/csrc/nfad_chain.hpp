@@ -21,6 +21,13 @@
 // All arithmetic is fp32 with the hardware exp2/log2/rcp; each primitive is written so that
 // its value AND its tangent stay accurate where the textbook formula cancels (1 - tanh^2,
 // s (1 - s), log(1 + e)).
+//
+// Three things keep a composed chain close to a hand-minimised kernel: constants are a type
+// of their own (Konst), so a binary operation with a constant costs one instruction and not
+// a product rule against a zero tangent; every node is evaluated for a storage tier (kWide,
+// as in nfad_math.hpp) and drops refinements that 16-bit storage cannot show; and two pairs
+// of primitives are recognised and evaluated in one step: tanh(softplus(.)), the core of
+// Mish, and 1 + erf(.), the core of GELU.
 #pragma once
 #include "nfad_math.hpp"
 
