@@ -35,6 +35,8 @@ def parse_args():
     ap.add_argument("--dtype", type=str, default=None, help="dtype of a multi-dtype config")
     ap.add_argument("--sets", type=int, default=0, help="rotating buffer sets (0 = enough for > 1 GiB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-stream-reference", action="store_true",
+                    help="skip the no-arithmetic streams (read, write, copy and the two kernels' patterns)")
     ap.add_argument("--calib-copy", type=int, default=0,
                     help="also launch this many plain device copies of x (n elements read, n written): the "
                          "known-size kernel that rocprofv3 FETCH_SIZE/WRITE_SIZE readings are scaled by")
@@ -188,6 +190,30 @@ def main():
                             "frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4),
                             "Gelem/s": round(n / (us * 1e-6) / 1e9, 1)}
 
+    # ---- what the memory system gives each traffic pattern on THIS part: the library's launch
+    # shape with the arithmetic taken out (nfad_probe_stream), same tensors, same protocol.  A
+    # reference, not a bound: a ratio above 1 means the kernel with arithmetic is the faster one.
+    stream_reference = None
+    if not args.no_stream_reference:
+        sink = torch.zeros(4, dtype=torch.int32, device=dev)
+        probes = {
+            "read_1": (lambda s, st: nfad.nfad_probe_stream([s["x"]], [], stream=st, sink=sink), 1),
+            "write_1": (lambda s, st: nfad.nfad_probe_stream([], [s["y"]], stream=st), 1),
+            "read_1_write_1": (lambda s, st: nfad.nfad_probe_stream([s["x"]], [s["y"]], stream=st), 2),
+            "read_1_write_2 (pattern of nfad_fwd)":
+                (lambda s, st: nfad.nfad_probe_stream([s["x"]], [s["y"], s["dydx"]], stream=st), 3),
+            "read_2_write_1 (pattern of nfad_bwd)":
+                (lambda s, st: nfad.nfad_probe_stream([s["gy"], s["dydx"]], [s["gx"]], stream=st), 3),
+        }
+        probe_us = time_kernels({k: f for k, (f, _) in probes.items()})
+        stream_reference = {k: {"us": round(probe_us[k], 2),
+                               "GB/s": round(w * n * es / (probe_us[k] * 1e-6) / 1e9, 1)}
+                           for k, (_, w) in probes.items()}
+        stream_reference["nfad_fwd_speed_vs_plain_stream"] = round(
+            probe_us["read_1_write_2 (pattern of nfad_fwd)"] / per_kernel["nfad_fwd"]["us"], 4)
+        stream_reference["nfad_bwd_speed_vs_plain_stream"] = round(
+            probe_us["read_2_write_1 (pattern of nfad_bwd)"] / per_kernel["nfad_bwd"]["us"], 4)
+
     # ---- context: the runtime's own device-to-device copy of the same tensor (n read + n written)
     for i in range(3):
         sets[i % nsets]["y"].copy_(sets[i % nsets]["x"])
@@ -331,7 +357,7 @@ def main():
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBPS, 4),
         "Gelem/s": round(6 * n / (ms_per_step * 1e-3) / 1e9, 1),
         "roofline": roofline, "cpu_baseline": cpu_baseline, "kernels": per_kernel, "summary": summary,
-        "reference_copy": reference_copy, "chains": chains,
+        "stream_reference": stream_reference, "reference_copy": reference_copy, "chains": chains,
     }
     print(json.dumps(out))
 

@@ -171,6 +171,73 @@ struct SaveAllBwdOp<kGeluTanh> {  // (g, x, t, h, s)
   }
 };
 
+// ------------------------------------------------------------------ streaming probes
+// The launch shape of the kernels above with the arithmetic taken out: N_IN tensors read,
+// N_OUT written, one block per tile, the same block sizes, unroll, cache hints and cap on
+// resident waves.  They measure what the memory system gives a traffic pattern on the part
+// at hand, so that a kernel's throughput can be read against its own pattern's ceiling.
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+template <int N_IN, int N_OUT>
+struct ProbeShape {
+  static constexpr int kThreads = N_IN <= 1 ? NFAD_THREADS_1IN : NFAD_THREADS_NIN;
+  static constexpr int kUnroll = NFAD_UNROLL;
+  static constexpr bool kNtLoad = N_IN == 1 ? (NFAD_NT_LOAD_1IN != 0) : (NFAD_NT_LOAD_NIN != 0);
+  static constexpr int kWavesRaw = NFAD_INFLIGHT_KIB / (kUnroll * (N_IN + N_OUT));
+  static constexpr int kWavesPerCu = kWavesRaw < 8 ? 8 : (kWavesRaw > 32 ? 32 : kWavesRaw);
+};
+struct ProbePtrs {
+  const u32x4* in[2];
+  u32x4* out[2];
+};
+
+template <int N_IN, int N_OUT>
+__global__ __launch_bounds__((ProbeShape<N_IN, N_OUT>::kThreads)) void probe_kernel(ProbePtrs p, size_t nvec) {
+  using Shape = ProbeShape<N_IN, N_OUT>;
+  constexpr int kThreads = Shape::kThreads, kUnroll = Shape::kUnroll;
+  const size_t base = (size_t)blockIdx.x * kThreads * kUnroll + threadIdx.x;
+  u32x4 v[kUnroll];
+#pragma unroll
+  for (int j = 0; j < kUnroll; ++j) {
+    const size_t idx = base + (size_t)j * kThreads;
+    // with nothing to read, write a pattern with busy bits (not a constant)
+    const unsigned h = (unsigned)idx * 2654435761u;
+    v[j] = u32x4{h, h ^ 0x9e3779b9u, h * 31u, ~h};
+    if (N_IN > 0 && idx < nvec) {
+      v[j] = stream_load<Shape::kNtLoad>(p.in[0] + idx);
+      if (N_IN > 1) v[j] ^= stream_load<Shape::kNtLoad>(p.in[1] + idx);
+    }
+  }
+  if constexpr (N_OUT > 0) {
+#pragma unroll
+    for (int j = 0; j < kUnroll; ++j) {
+      const size_t idx = base + (size_t)j * kThreads;
+      if (idx < nvec) {
+        stream_store(p.out[0] + idx, v[j]);
+        if (N_OUT > 1) stream_store(p.out[1] + idx, ~v[j]);
+      }
+    }
+  } else {
+    // keep the loads alive: one 16-byte write that practically never happens
+    u32x4 acc = v[0];
+#pragma unroll
+    for (int j = 1; j < kUnroll; ++j) acc ^= v[j];
+    if (acc.x == 0x7fc12345u && acc.y == 0x7fc54321u && acc.z == 0x12345678u && acc.w == 0x87654321u) p.out[0][0] = acc;
+  }
+}
+
+template <int N_IN, int N_OUT>
+static int launch_probe(const ProbePtrs& p, size_t nvec, hipStream_t stream) {
+  using Shape = ProbeShape<N_IN, N_OUT>;
+  const size_t tile = (size_t)Shape::kThreads * Shape::kUnroll;
+  const size_t grid = (nvec + tile - 1) / tile;
+  if (grid == 0) return NFAD_OK;
+  if (grid > max_grid()) return NFAD_ELAUNCH;   // probes do not stride: 2^24 tiles is 64 GiB per tensor
+  const unsigned lds = lds_reservation(Shape::kWavesPerCu, Shape::kThreads, device_info().lds_per_cu);
+  hipLaunchKernelGGL((probe_kernel<N_IN, N_OUT>), dim3((unsigned)grid), dim3(Shape::kThreads), lds, stream, p, nvec);
+  return hipGetLastError() == hipSuccess ? NFAD_OK : NFAD_ELAUNCH;
+}
+
 }  // namespace nfad
 
 using namespace nfad;
@@ -328,5 +395,36 @@ int nfad_version(void) { return 100; }
 #ifdef NFAD_EXPERIMENT
 void nfad_experiment_set_waves(int waves) { nfad::g_waves_experiment = waves; }
 #endif
+
+int nfad_probe_stream(int n_in, int n_out, const void* const* in, void* const* out, size_t bytes, void* stream) {
+  using namespace nfad;
+  if (n_in < 0 || n_in > 2 || n_out < 0 || n_out > 2 || n_in + n_out == 0) return NFAD_EINVAL_KIND;
+  if ((n_in > 0 && !in) || !out) return NFAD_ENULL;
+  ProbePtrs p = {{nullptr, nullptr}, {nullptr, nullptr}};
+  for (int i = 0; i < n_in; ++i) {
+    if (!in[i]) return NFAD_ENULL;
+    if ((uintptr_t)in[i] & 15u) return NFAD_EALIGN;
+    p.in[i] = static_cast<const u32x4*>(in[i]);
+  }
+  for (int o = 0; o < (n_out > 0 ? n_out : 1); ++o) {   // with n_out == 0, out[0] is the 16-byte sink
+    if (!out[o]) return NFAD_ENULL;
+    if ((uintptr_t)out[o] & 15u) return NFAD_EALIGN;
+    p.out[o] = static_cast<u32x4*>(out[o]);
+  }
+  if (bytes & 15u) return NFAD_EALIGN;
+  const size_t nvec = bytes / 16;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  switch (n_in * 3 + n_out) {
+    case 0 * 3 + 1: return launch_probe<0, 1>(p, nvec, st);
+    case 0 * 3 + 2: return launch_probe<0, 2>(p, nvec, st);
+    case 1 * 3 + 0: return launch_probe<1, 0>(p, nvec, st);
+    case 1 * 3 + 1: return launch_probe<1, 1>(p, nvec, st);
+    case 1 * 3 + 2: return launch_probe<1, 2>(p, nvec, st);
+    case 2 * 3 + 0: return launch_probe<2, 0>(p, nvec, st);
+    case 2 * 3 + 1: return launch_probe<2, 1>(p, nvec, st);
+    case 2 * 3 + 2: return launch_probe<2, 2>(p, nvec, st);
+  }
+  return NFAD_EINVAL_KIND;
+}
 
 }  // extern "C"
