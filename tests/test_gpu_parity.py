@@ -203,6 +203,40 @@ def test_every_16bit_pattern(dtype):
     print(f"\n[exhaustive {dtype}] strict-ulp report (max_ulp_y, n>1, max_ulp_d, n>1): {report}")
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_every_16bit_pattern_through_the_baselines(dtype):
+    """The recomputation and save-all kernels on every finite 16-bit input with |x| <= 128
+    (upstream gradient 1, so backward must reproduce the derivative itself)."""
+    from parity import tolerance
+    td = DTYPES[dtype]
+    bits = torch.arange(65536, dtype=torch.int32).to(torch.int16)
+    x_all = bits.view(td)
+    xf = x_all.to(torch.float64)
+    x = x_all[torch.isfinite(xf) & (xf.abs() <= 128.0)].contiguous()
+    x64 = inputs.storage_to_f64(x)
+    xd = dev(x)
+    one = torch.ones_like(xd)
+    one64 = np.ones_like(x64)
+    for kind in nfad.KINDS:
+        y, gx = torch.empty_like(xd), torch.empty_like(xd)
+        nfad.nfad_recompute_fwd(kind, xd, y)
+        nfad.nfad_recompute_bwd(kind, one, xd, gx)
+        compare(y, oracle.recompute_fwd(kind, x64), td, f"exhaustive recompute fwd kind={kind} {dtype}")
+        compare(gx, oracle.recompute_bwd(kind, one64, x64), td, f"exhaustive recompute bwd kind={kind} {dtype}")
+        k = nfad.nfad_saveall_num_saved(kind)
+        y_ref, saved_ref = oracle.saveall_fwd(kind, x64)
+        saved = [xd] + [torch.full_like(xd, float("nan")) for _ in range(k - 1)]
+        nfad.nfad_saveall_fwd(kind, xd, y, saved)
+        compare(y, y_ref, td, f"exhaustive saveall fwd y kind={kind} {dtype}")
+        for j in range(1, k):
+            compare(saved[j], saved_ref[j], td, f"exhaustive saveall saved[{j}] kind={kind} {dtype}")
+        saved_st = [x] + [inputs.to_storage(v.astype(np.float32), dtype) for v in saved_ref[1:]]
+        gx_ref = oracle.saveall_bwd(kind, one64, [inputs.storage_to_f64(v) for v in saved_st])
+        nfad.nfad_saveall_bwd(kind, one, [dev(v) for v in saved_st], gx)
+        tol = tolerance(torch.from_numpy(gx_ref), td).numpy() + 4e-6 * np.maximum(1.0, np.abs(x64))
+        assert np.all(np.abs(gx.double().cpu().numpy() - gx_ref) <= tol), f"exhaustive saveall bwd kind={kind} {dtype}"
+
+
 # ------------------------------------------------------------------ edge cases
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_tiny_and_empty_sizes(dtype):
