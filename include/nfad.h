@@ -167,19 +167,6 @@ int nfad_chain_fwd_multi(int chain_id, const void* x, void* const* y, void* cons
 int nfad_bwd_multi(const void* const* gy, const void* const* dydx, int m, void* gx, size_t n,
                    int dtype, void* stream);
 
-/* Streaming probe (a measurement aid, not part of the paper's method): moves `bytes` per tensor
- * with the launch shape of the kernels above (block size, 16-byte accesses, cache hints, cap
- * on resident waves) and no arithmetic, so that a kernel's throughput can be read against the
- * ceiling of its own traffic pattern on the part at hand.  n_in tensors are read (0..2,
- * device pointers in the host array `in`), n_out are written (0..2, host array `out`); the
- * data written is the XOR of what was read (its complement in out[1]), or an index pattern
- * when nothing is read.  With n_out == 0, out[0] must still point to 16 writable device
- * bytes (a sink that is practically never written).  All pointers 16-byte aligned and `bytes`
- * a multiple of 16 (NFAD_EALIGN otherwise); NFAD_EINVAL_KIND for an unsupported (n_in, n_out);
- * NFAD_ELAUNCH beyond 2^24 tiles of 4 KiB.  Asynchronous on `stream`, capturable. */
-int nfad_probe_stream(int n_in, int n_out, const void* const* in, void* const* out, size_t bytes,
-                      void* stream);
-
 /* Static, NUL-terminated description of a status code (never NULL). */
 const char* nfad_status_string(int status);
 

@@ -59,7 +59,6 @@ def lib() -> ctypes.CDLL:
         L.nfad_chain_num_outputs.argtypes = [ci]
         L.nfad_chain_fwd_multi.argtypes = [ci, vp, vpp, vpp, sz, ci, vp]
         L.nfad_bwd_multi.argtypes = [vpp, vpp, ci, vp, sz, ci, vp]
-        L.nfad_probe_stream.argtypes = [ci, ci, vpp, vpp, sz, vp]
         L.nfad_chain_log.restype = ctypes.c_char_p
         L.nfad_status_string.argtypes = [ci]
         L.nfad_status_string.restype = ctypes.c_char_p
@@ -67,7 +66,7 @@ def lib() -> ctypes.CDLL:
                      "nfad_saveall_num_saved", "nfad_saveall_fwd", "nfad_saveall_bwd", "nfad_version",
                      "nfad_chain_count", "nfad_chain_fwd", "nfad_chain_compile", "nfad_chain_release",
                      "nfad_chain_compile_multi", "nfad_chain_num_outputs", "nfad_chain_fwd_multi",
-                     "nfad_bwd_multi", "nfad_probe_stream"):
+                     "nfad_bwd_multi"):
             getattr(L, name).restype = ci
         _lib = L
     return _lib
@@ -214,24 +213,6 @@ def nfad_bwd_multi(gys, dydxs, gx, stream=None) -> None:
     n, dt = _marshal(gx, *gys, *dydxs)
     _check(lib().nfad_bwd_multi(_ptr_array(gys), _ptr_array(dydxs), len(gys), gx.data_ptr(), n, dt,
                                 _stream(stream)), "nfad_bwd_multi")
-
-
-def nfad_probe_stream(ins, outs, nbytes=None, stream=None, sink=None) -> None:
-    """No-arithmetic stream with the library's launch shape: reads the tensors `ins`, writes `outs`
-    (byte sizes must agree); with no output, `sink` must be a device tensor of >= 16 bytes."""
-    tensors = list(ins) + list(outs)
-    for t in tensors + ([sink] if sink is not None else []):
-        if not t.is_cuda or not t.is_contiguous():
-            raise ValueError("libnfad works on contiguous device memory only")
-    sizes = {t.numel() * t.element_size() for t in tensors}
-    if len(sizes) != 1:
-        raise ValueError("all tensors of one probe must have the same size in bytes")
-    nbytes = sizes.pop() if nbytes is None else int(nbytes)
-    out_list = list(outs) if outs else [sink]
-    if out_list[0] is None:
-        raise ValueError("a read-only probe needs a 16-byte sink")
-    _check(lib().nfad_probe_stream(len(ins), len(outs), _ptr_array(list(ins)) if ins else None,
-                                   _ptr_array(out_list), nbytes, _stream(stream)), "nfad_probe_stream")
 
 
 def nfad_chain_release(chain_id: int) -> None:

@@ -157,8 +157,9 @@ struct Compiled {
   std::string program, name;
   int m = 1;                                              // number of outputs (chains over the same x)
   hipModule_t module = nullptr;
-  hipFunction_t vec[3] = {nullptr, nullptr, nullptr};     // indexed by nfad_dtype_t
-  hipFunction_t scalar[3] = {nullptr, nullptr, nullptr};
+  hipFunction_t vec[3] = {nullptr, nullptr, nullptr};     // indexed by nfad_dtype_t: the shape for large launches,
+  hipFunction_t vec_small[3] = {nullptr, nullptr, nullptr};   // ... the one for small launches,
+  hipFunction_t scalar[3] = {nullptr, nullptr, nullptr};  // ... and the element-at-a-time kernel
   bool live = false;
 };
 static std::mutex g_mu;
@@ -241,10 +242,12 @@ static int compile(const char* const* programs, int m, int* chain_id) {
     g_log = "hiprtcCreateProgram failed";
     return NFAD_ECOMPILE;
   }
-  std::string names[6];
+  std::string names[9];
   for (int t = 0; t < 3; ++t) {
-    names[t] = "nfad::ew_vec_kernel<" + op + ", " + kTypeNames[t] + ">";
+    const std::string rule = "nfad::ShapeRule<1, " + std::to_string(2 * m) + ", " + kTypeNames[t] + ">";
+    names[t] = "nfad::ew_vec_kernel<" + op + ", " + kTypeNames[t] + ", " + rule + "::Large>";
     names[3 + t] = "nfad::ew_scalar_kernel<" + op + ", " + kTypeNames[t] + ">";
+    names[6 + t] = "nfad::ew_vec_kernel<" + op + ", " + kTypeNames[t] + ", " + rule + "::Small>";
   }
   for (auto& nm : names) hiprtcAddNameExpression(prog, nm.c_str());
 
@@ -274,10 +277,11 @@ static int compile(const char* const* programs, int m, int* chain_id) {
   c->program = joined;
   c->m = m;
   bool ok = hipModuleLoadData(&c->module, code.data()) == hipSuccess;
-  for (int t = 0; ok && t < 6; ++t) {
+  for (int t = 0; ok && t < 9; ++t) {
     const char* lowered = nullptr;
+    hipFunction_t* slot = t < 3 ? &c->vec[t] : (t < 6 ? &c->scalar[t - 3] : &c->vec_small[t - 6]);
     ok = hiprtcGetLoweredName(prog, names[t].c_str(), &lowered) == HIPRTC_SUCCESS && lowered &&
-         hipModuleGetFunction(t < 3 ? &c->vec[t] : &c->scalar[t - 3], c->module, lowered) == hipSuccess;
+         hipModuleGetFunction(slot, c->module, lowered) == hipSuccess;
   }
   hiprtcDestroyProgram(&prog);
   if (!ok) {
@@ -327,8 +331,8 @@ static int forward_m(const Compiled* c, const void* x, void* const* y, void* con
     return hipModuleLaunchKernel(f, g.grid, 1, 1, g.threads, 1, 1, g.lds, s, params, nullptr);
   };
   return launch_planned(
-      p, n, elem_size(dtype),
-      [&](const P& q, size_t m, Geometry g) { return enqueue(c->vec[dtype], q, m, g); },
+      p, n, dtype,
+      [&](const P& q, size_t m, Geometry g) { return enqueue(g.small ? c->vec_small[dtype] : c->vec[dtype], q, m, g); },
       [&](const P& q, size_t m, Geometry g) { return enqueue(c->scalar[dtype], q, m, g); });
 }
 

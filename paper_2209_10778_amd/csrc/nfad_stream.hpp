@@ -35,25 +35,6 @@ static DeviceInfo device_info() {
   return cached[dev];
 }
 
-// NFAD_WAVES_PER_CU (environment, read once): tuning aid that replaces the built-in cap on
-// resident waves per compute unit; 0 disables the cap.
-#ifdef NFAD_EXPERIMENT   /* experiment builds only: the override can be changed between launches */
-static int g_waves_experiment = -1;
-static int waves_per_cu_override() { return g_waves_experiment; }
-#else
-static int waves_per_cu_override() {
-  static int cached = -2;
-  int v = __atomic_load_n(&cached, __ATOMIC_RELAXED);
-  if (v == -2) {
-    const char* s = getenv("NFAD_WAVES_PER_CU");
-    v = s ? atoi(s) : -1;
-    if (v < -1 || v > 64) v = -1;
-    __atomic_store_n(&cached, v, __ATOMIC_RELAXED);
-  }
-  return v;
-}
-#endif
-
 // Largest grid of the vector kernel.  One block per tile up to this many blocks; beyond it the
 // kernel's grid stride takes over.  2^24 blocks keeps grid x block below 2^32 threads.
 // NFAD_MAX_GRID (environment, read once) lowers it, which is how the striding path is tested.
@@ -81,27 +62,42 @@ static unsigned lds_reservation(int waves_per_cu, int threads, int lds_per_cu) {
   return (unsigned)((lds_per_cu / blocks) & ~1023);
 }
 
-// Grid, block and idle-LDS reservation of a launch.
+// Grid, block and idle-LDS reservation of a launch, and which of the operation's two shapes it uses.
 struct Geometry {
   unsigned grid, threads, lds;
+  bool small;
 };
-template <int NIN, int NOUT>
-static Geometry vec_geometry(size_t n, int elems_per_vec) {
-  using Shape = LaunchShape<NIN, NOUT>;
+template <class Sh>
+static Geometry shape_geometry(size_t n, int elems_per_vec, int waves_per_cu, bool small) {
   const size_t nvec = n / (size_t)elems_per_vec;
-  size_t grid = nvec / ((size_t)Shape::kThreads * Shape::kUnroll);   // one block per full tile
+  size_t grid = nvec / ((size_t)Sh::kThreads * Sh::kUnroll);   // one block per full tile
   if (grid == 0) grid = 1;
   if (grid > max_grid()) grid = max_grid();
-  int waves = waves_per_cu_override();
-  if (waves < 0) waves = Shape::kWavesPerCu;
-  return {(unsigned)grid, (unsigned)Shape::kThreads,
-          lds_reservation(waves, Shape::kThreads, device_info().lds_per_cu)};
+  return {(unsigned)grid, (unsigned)Sh::kThreads, lds_reservation(waves_per_cu, Sh::kThreads, device_info().lds_per_cu),
+          small};
+}
+template <int NIN, int NOUT, typename T>
+static Geometry rule_geometry(size_t n) {
+  using R = ShapeRule<NIN, NOUT, T>;
+  constexpr int kVec = 16 / (int)sizeof(T);
+  if (R::kTwoShapes && (unsigned long long)n * sizeof(T) * (NIN + NOUT) < R::kSmallBytes)
+    return shape_geometry<typename R::Small>(n, kVec, R::kSmallWavesPerCu, true);
+  return shape_geometry<typename R::Large>(n, kVec, R::kLargeWavesPerCu, false);
+}
+// Geometry of the vector kernel of an operation with NIN inputs and NOUT outputs on `dtype` storage.
+template <int NIN, int NOUT>
+static Geometry default_geometry(int dtype, size_t n) {
+  switch (dtype) {
+    case NFAD_F32: return rule_geometry<NIN, NOUT, float>(n);
+    case NFAD_F16: return rule_geometry<NIN, NOUT, _Float16>(n);
+    default: return rule_geometry<NIN, NOUT, __bf16>(n);
+  }
 }
 static Geometry scalar_geometry(size_t n) {
   size_t grid = (n + kScalarThreads - 1) / kScalarThreads;
   const size_t cap = (size_t)device_info().cus * 32;
   if (grid > cap) grid = cap;
-  return {(unsigned)grid, (unsigned)kScalarThreads, 0u};
+  return {(unsigned)grid, (unsigned)kScalarThreads, 0u, false};
 }
 // How a call is carried out.  The 16-byte vector kernel needs every pointer 16-byte aligned.
 // If all pointers are misaligned by the SAME amount (a view such as t[1:] of aligned tensors),
@@ -133,8 +129,9 @@ static Ptrs<NIN, NOUT> advanced(const Ptrs<NIN, NOUT>& p, size_t bytes) {
 // Runs a call according to its plan.  launch_vec(ptrs, n, geometry) and launch_scalar(ptrs, n,
 // geometry) enqueue the two kernels and return a hipError_t.
 template <int NIN, int NOUT, class LaunchVec, class LaunchScalar>
-static int launch_planned(const Ptrs<NIN, NOUT>& p, size_t n, size_t elem_bytes, LaunchVec launch_vec,
+static int launch_planned(const Ptrs<NIN, NOUT>& p, size_t n, int dtype, LaunchVec launch_vec,
                           LaunchScalar launch_scalar) {
+  const size_t elem_bytes = dtype == NFAD_F32 ? 4 : 2;
   const Plan plan = make_plan(p, n, elem_bytes);
   hipError_t e = hipSuccess;
   if (!plan.vec) {
@@ -143,23 +140,27 @@ static int launch_planned(const Ptrs<NIN, NOUT>& p, size_t n, size_t elem_bytes,
     if (plan.head) e = launch_scalar(p, plan.head, scalar_geometry(plan.head));
     if (e == hipSuccess) {
       const size_t rest = n - plan.head;
-      e = launch_vec(advanced(p, plan.head * elem_bytes), rest, vec_geometry<NIN, NOUT>(rest, (int)(16 / elem_bytes)));
+      e = launch_vec(advanced(p, plan.head * elem_bytes), rest, default_geometry<NIN, NOUT>(dtype, rest));
     }
   }
   return e == hipSuccess ? NFAD_OK : NFAD_ELAUNCH;
 }
 
-template <class Op, typename T>
+template <class Op, typename T, int DTYPE>
 static int launch(const void* const (&in)[Op::kIn], void* const (&out)[Op::kOut], size_t n,
                   hipStream_t stream) {
   using P = Ptrs<Op::kIn, Op::kOut>;
+  using R = ShapeRule<Op::kIn, Op::kOut, T>;
   P p;
   for (int i = 0; i < Op::kIn; ++i) p.in[i] = in[i];
   for (int o = 0; o < Op::kOut; ++o) p.out[o] = out[o];
   return launch_planned(
-      p, n, sizeof(T),
+      p, n, DTYPE,
       [stream](const P& q, size_t m, Geometry g) {
-        hipLaunchKernelGGL((ew_vec_kernel<Op, T>), dim3(g.grid), dim3(g.threads), g.lds, stream, q, m);
+        if (R::kTwoShapes && g.small)
+          hipLaunchKernelGGL((ew_vec_kernel<Op, T, typename R::Small>), dim3(g.grid), dim3(g.threads), g.lds, stream, q, m);
+        else
+          hipLaunchKernelGGL((ew_vec_kernel<Op, T, typename R::Large>), dim3(g.grid), dim3(g.threads), g.lds, stream, q, m);
         return hipGetLastError();
       },
       [stream](const P& q, size_t m, Geometry g) {
@@ -173,9 +174,9 @@ static int launch_dtype(int dtype, const void* const (&in)[Op::kIn], void* const
                         size_t n, void* stream) {
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   switch (dtype) {
-    case NFAD_F32: return launch<Op, float>(in, out, n, s);
-    case NFAD_F16: return launch<Op, _Float16>(in, out, n, s);
-    case NFAD_BF16: return launch<Op, __bf16>(in, out, n, s);
+    case NFAD_F32: return launch<Op, float, NFAD_F32>(in, out, n, s);
+    case NFAD_F16: return launch<Op, _Float16, NFAD_F16>(in, out, n, s);
+    case NFAD_BF16: return launch<Op, __bf16, NFAD_BF16>(in, out, n, s);
   }
   return NFAD_EINVAL_DTYPE;
 }

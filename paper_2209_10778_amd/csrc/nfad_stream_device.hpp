@@ -14,44 +14,50 @@
 #include <hip/hip_runtime.h>
 #endif
 
-// Launch-shape overrides for experiments (the defaults below are the measured choices).
-#ifndef NFAD_THREADS_1IN   /* block size of kernels that read one tensor  */
-#define NFAD_THREADS_1IN 128
-#endif
-#ifndef NFAD_THREADS_NIN   /* block size of kernels that read several     */
-#define NFAD_THREADS_NIN 64
-#endif
-#ifndef NFAD_UNROLL        /* 16-byte accesses in flight per lane and tensor */
-#define NFAD_UNROLL 2
-#endif
-#ifndef NFAD_NT_LOAD_1IN   /* nontemporal loads, one-input kernels        */
-#define NFAD_NT_LOAD_1IN 0
-#endif
-#ifndef NFAD_NT_LOAD_NIN   /* nontemporal loads, several-input kernels    */
-#define NFAD_NT_LOAD_NIN 1
-#endif
-#ifndef NFAD_INFLIGHT_KIB  /* target KiB of 16-byte accesses in flight per compute unit */
-#define NFAD_INFLIGHT_KIB 96
-#endif
-
 namespace nfad {
 
-// Launch shape of a streaming kernel with NIN input and NOUT output tensors.
-//
-// The path is bound by HBM, and HBM runs best when just enough requests are in flight to
-// cover its latency (bandwidth x latency ~ 16 MB over the chip, ~64 KiB per compute unit):
-// more than that only lengthens the queues in front of the DRAM banks and costs row hits
-// and read/write turnarounds.  So every kernel uses small blocks, kUnroll independent
-// 16-byte accesses per lane and tensor, and a cap on resident waves per compute unit of
-//     kInflightKiB / (kUnroll * (NIN + NOUT))        (one wave64 access = 1 KiB),
-// enforced by reserving an idle slice of the 160 KiB LDS per block at launch.
-template <int NIN, int NOUT>
-struct LaunchShape {
-  static constexpr int kThreads = NIN == 1 ? NFAD_THREADS_1IN : NFAD_THREADS_NIN;
-  static constexpr int kUnroll = NFAD_UNROLL;
-  static constexpr bool kNtLoad = NIN == 1 ? (NFAD_NT_LOAD_1IN != 0) : (NFAD_NT_LOAD_NIN != 0);
-  static constexpr int kWavesRaw = NFAD_INFLIGHT_KIB / (kUnroll * (NIN + NOUT));
-  static constexpr int kWavesPerCu = kWavesRaw < 8 ? 8 : (kWavesRaw > 32 ? 32 : kWavesRaw);
+// ------------------------------------------------------------------ launch shape
+// The compile-time half of a launch shape: block size, independent 16-byte accesses in flight
+// per lane and tensor, and whether loads carry the nontemporal hint.  (The run-time half, the
+// cap on resident waves per compute unit, is applied by the host through an idle LDS
+// reservation.)
+template <int THREADS, int UNROLL, bool NT_LOAD>
+struct Shape {
+  static constexpr int kThreads = THREADS;
+  static constexpr int kUnroll = UNROLL;
+  static constexpr bool kNtLoad = NT_LOAD;
+};
+
+// The shapes the library's kernels run in, chosen from interleaved in-process sweeps over block
+// size x unroll x load hint x cap on resident waves, with the arithmetic in place, on tensors
+// from 12 MB to 805 MB per launch.  The path is bound by HBM, and HBM runs best when just
+// enough requests are in flight to cover its latency: more only lengthens the queues in front
+// of the DRAM banks.  The simplest stream wins almost everywhere: one-wave blocks, ONE 16-byte
+// access per lane and tensor, nontemporal loads.
+//  * Kernels that read several tensors (backward passes) and one-read/one-write kernels run it
+//    with no cap on resident waves: best or within 1-2 % of best at every size.
+//  * Kernels that read one tensor and write several (the forward pass of the method) run it
+//    capped at 20 waves per compute unit for fp32 storage and 24 for 16-bit storage (twice the
+//    arithmetic per byte keeps a wave alive longer).  A launch that moves less than 96 MB is
+//    over before a steady state forms, and then what counts is how fast the grid is handed
+//    out: four times fewer, fatter blocks (two waves, two accesses per lane) and no cap.
+template <bool C, class A, class B>
+struct SelectType {
+  using type = A;
+};
+template <class A, class B>
+struct SelectType<false, A, B> {
+  using type = B;
+};
+template <int NIN, int NOUT, typename T>
+struct ShapeRule {
+  static constexpr bool kFanOut = NIN == 1 && NOUT >= 2;
+  using Large = Shape<64, 1, true>;
+  using Small = typename SelectType<kFanOut, Shape<128, 2, true>, Large>::type;
+  static constexpr int kLargeWavesPerCu = kFanOut ? (sizeof(T) == 4 ? 20 : 24) : 0;   // 0 = no cap
+  static constexpr int kSmallWavesPerCu = 0;
+  static constexpr bool kTwoShapes = kFanOut;
+  static constexpr unsigned long long kSmallBytes = 96ull << 20;   // bytes moved per launch
 };
 
 // ------------------------------------------------------------------ storage formats
@@ -116,17 +122,15 @@ static constexpr int kScalarThreads = 256;
 // unguarded; the one partial tile and the < kVec scalar tail elements are taken by a single
 // block.  The kernel uses no LDS: the dynamic LDS size of the launch only limits how many
 // blocks fit on a compute unit.
-template <class Op, typename T>
-__global__ __launch_bounds__((LaunchShape<Op::kIn, Op::kOut>::kThreads)) void ew_vec_kernel(
-    Ptrs<Op::kIn, Op::kOut> p, size_t n) {
+template <class Op, typename T, class Sh>
+__global__ __launch_bounds__((Sh::kThreads)) void ew_vec_kernel(Ptrs<Op::kIn, Op::kOut> p, size_t n) {
   using S = Storage<T>;
   using Vec = typename S::Vec;
-  using Shape = LaunchShape<Op::kIn, Op::kOut>;
   constexpr int kVec = S::kVec;
   constexpr bool kWide = sizeof(T) == 4;
-  constexpr int kThreads = Shape::kThreads;
-  constexpr int kUnroll = Shape::kUnroll;
-  constexpr bool kNt = Shape::kNtLoad;
+  constexpr int kThreads = Sh::kThreads;
+  constexpr int kUnroll = Sh::kUnroll;
+  constexpr bool kNt = Sh::kNtLoad;
   constexpr size_t kTile = (size_t)kThreads * kUnroll;
   const size_t nvec = n / kVec;
   const size_t full_tiles = nvec / kTile;

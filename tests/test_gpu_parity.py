@@ -500,35 +500,3 @@ def test_beyond_32bit_element_count():
         compare(d[start:start + W], d_ref, td, f"big d @{start}")
     del xd, y, d
     torch.cuda.empty_cache()
-
-
-# ------------------------------------------------------------------ streaming probes (measurement aid)
-def test_stream_probes_move_exactly_what_they_say():
-    nbytes = (3 * 8192 + 77) * 16
-    a = torch.randint(0, 2 ** 31 - 1, (nbytes // 4,), dtype=torch.int32, device=DEV)
-    b = torch.randint(0, 2 ** 31 - 1, (nbytes // 4,), dtype=torch.int32, device=DEV)
-    o1, o2 = torch.zeros_like(a), torch.zeros_like(a)
-    sink = torch.zeros(4, dtype=torch.int32, device=DEV)
-    nfad.nfad_probe_stream([a], [o1])                       # copy
-    assert torch.equal(o1, a)
-    nfad.nfad_probe_stream([a, b], [o1])                    # two reads, one write: XOR
-    assert torch.equal(o1, a ^ b)
-    nfad.nfad_probe_stream([a], [o1, o2])                   # one read, two writes: value and complement
-    assert torch.equal(o1, a) and torch.equal(o2, ~a)
-    nfad.nfad_probe_stream([a], [], sink=sink)              # read only: nothing visible changes
-    assert int(sink.abs().sum()) == 0
-    o1.zero_()
-    nfad.nfad_probe_stream([], [o1])                        # write only: an index pattern, not a constant
-    v = o1.view(-1, 4)[:, 0].to(torch.int64) & 0xFFFFFFFF
-    expect = (torch.arange(v.numel(), device=DEV, dtype=torch.int64) * 2654435761) & 0xFFFFFFFF
-    assert torch.equal(v, expect)
-    L = nfad.lib()
-    A = 1 << 20
-    import ctypes
-    arr = (ctypes.c_void_p * 2)(A, A + 4096)
-    assert L.nfad_probe_stream(3, 1, arr, arr, 4096, None) == 1      # unsupported pattern
-    assert L.nfad_probe_stream(0, 0, arr, arr, 4096, None) == 1
-    assert L.nfad_probe_stream(1, 1, arr, arr, 4097, None) == 4      # bytes not a multiple of 16
-    bad = (ctypes.c_void_p * 2)(A + 8, A + 4096)
-    assert L.nfad_probe_stream(1, 1, bad, arr, 4096, None) == 4      # misaligned pointer
-    assert L.nfad_probe_stream(1, 1, None, arr, 4096, None) == 3
