@@ -18,7 +18,8 @@
  *             shape (NCHW, row-major, ...) is irrelevant: the operation is
  *             element-wise.  `saved` is a HOST array of device pointers.
  * Ownership : the caller owns every buffer.  The library never allocates, frees or
- *             keeps a pointer, and has no state (thread-safe, re-entrant).
+ *             keeps a pointer, and has no state apart from the table of run-time compiled
+ *             chains (thread-safe, re-entrant).
  * Stream    : `stream` is a hipStream_t passed as void*; NULL is the default stream.
  *             Calls enqueue work and return; they never synchronise, allocate or copy,
  *             so they may be captured into a HIP graph.
@@ -129,20 +130,32 @@ int nfad_chain_fwd(int chain_id, const void* x, void* y, void* dydx, size_t n, i
  * (Sec. III-B, Sec. IV), which finds a chain of fad operations and replaces its forward and
  * backward passes.  `program` is ANY chain in the postfix notation above (tokens separated
  * by blanks: x, decimal constants and the primitive names listed above; at most
- * 256 tokens; must use x and leave exactly one value).  The library compiles one fused
- * forward kernel for it on the current device (hiprtc; about a second) and returns a chain
- * id >= NFAD_CHAIN_JIT_BASE in *chain_id, valid for nfad_chain_fwd / _name / _program on
- * that device until released.  This is the one stateful part of the library: the table of
- * compiled chains is process-wide and protected by a mutex.
+ * 256 tokens and 24 constants; must use x and leave exactly one value).  The library compiles
+ * one fused forward kernel for it on the current device (hiprtc; a fraction of a second) and
+ * returns a chain id >= NFAD_CHAIN_JIT_BASE in *chain_id, valid for nfad_chain_fwd / _name /
+ * _program on that device until released.
+ * Constants are arguments of the kernel, not part of it (Sec. III-A "binary operation with a
+ * constant"): programs that differ only in their numbers share ONE compiled kernel, so
+ * compiling `x 0.1 *` after `x 0.2 *` costs no compiler run.  (Sub-expressions without x are
+ * folded on the host; only 0, +-1, +-2 and +-0.5 are compiled in.)
+ * This is the one stateful part of the library: a process-wide table of at most 4096 LIVE
+ * chains, protected by a mutex; a released chain's id is handed out again, and a kernel is
+ * unloaded with the last chain that uses it.
  *   nfad_chain_compile  NFAD_EPROGRAM for a malformed program (checked on the host before
  *                       any compiler or HIP call), NFAD_ECOMPILE if compiling or loading fails
- *   nfad_chain_release  unloads the kernel; the caller must first wait for launches of that
+ *                       or if the table is full (checked before compiling)
+ *   nfad_chain_release  frees the id; the caller must first wait for launches of that
  *                       chain to finish.  NFAD_EINVAL_KIND for an id that is not live
+ *   nfad_chain_kernel   identifier (>= 0) of the compiled kernel behind a run-time chain: equal
+ *                       for chains that share a kernel; -1 for a built-in or dead id
  *   nfad_chain_log      the calling thread's message from its last nfad_chain_compile
- *                       (parse error or compiler log; empty string if none) */
+ *                       (parse error or compiler log; empty string if none)
+ * Results are finite wherever the true value is representable and every intermediate
+ * exponential stays finite or overflows only into a denominator (then the limit is returned). */
 #define NFAD_CHAIN_JIT_BASE 1000
 int nfad_chain_compile(const char* program, int* chain_id);
 int nfad_chain_release(int chain_id);
+int nfad_chain_kernel(int chain_id);
 const char* nfad_chain_log(void);
 
 /* One source, several outputs (Sec. II-D "R^1 -> R^M", Sec. IV-A): m chains over the same x,

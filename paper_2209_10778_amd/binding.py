@@ -55,6 +55,7 @@ def lib() -> ctypes.CDLL:
         L.nfad_chain_program.restype = ctypes.c_char_p
         L.nfad_chain_compile.argtypes = [ctypes.c_char_p, ctypes.POINTER(ci)]
         L.nfad_chain_release.argtypes = [ci]
+        L.nfad_chain_kernel.argtypes = [ci]
         L.nfad_chain_compile_multi.argtypes = [ctypes.POINTER(ctypes.c_char_p), ci, ctypes.POINTER(ci)]
         L.nfad_chain_num_outputs.argtypes = [ci]
         L.nfad_chain_fwd_multi.argtypes = [ci, vp, vpp, vpp, sz, ci, vp]
@@ -66,7 +67,7 @@ def lib() -> ctypes.CDLL:
                      "nfad_saveall_num_saved", "nfad_saveall_fwd", "nfad_saveall_bwd", "nfad_version",
                      "nfad_chain_count", "nfad_chain_fwd", "nfad_chain_compile", "nfad_chain_release",
                      "nfad_chain_compile_multi", "nfad_chain_num_outputs", "nfad_chain_fwd_multi",
-                     "nfad_bwd_multi"):
+                     "nfad_bwd_multi", "nfad_chain_kernel"):
             getattr(L, name).restype = ci
         _lib = L
     return _lib
@@ -213,6 +214,12 @@ def nfad_bwd_multi(gys, dydxs, gx, stream=None) -> None:
     n, dt = _marshal(gx, *gys, *dydxs)
     _check(lib().nfad_bwd_multi(_ptr_array(gys), _ptr_array(dydxs), len(gys), gx.data_ptr(), n, dt,
                                 _stream(stream)), "nfad_bwd_multi")
+
+
+def nfad_chain_kernel(chain_id: int) -> int:
+    """Identifier of the compiled kernel behind a run-time chain (shared by chains that differ only
+    in constants); -1 for a built-in or dead id."""
+    return int(lib().nfad_chain_kernel(int(chain_id)))
 
 
 def nfad_chain_release(chain_id: int) -> None:

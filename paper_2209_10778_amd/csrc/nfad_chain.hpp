@@ -13,7 +13,7 @@
 // folded away by the compiler (the paper's NY->YN shortcut, Sec. IV-B "Efficiency").
 //
 //   using Mish = Mul<X, Tanh<Softplus<X>>>;          // x * tanh(softplus(x))
-//   Dual r = to_dual(Mish::eval<true>(seed(x)));     // r.v = y, r.d = dy/dx
+//   Dual r = to_dual(Mish::eval<true>(seed(x), args));   // r.v = y, r.d = dy/dx
 //
 // Shared sub-expressions are written twice in the type but evaluated once: everything is
 // inlined and pure, so the compiler merges them.
@@ -37,6 +37,14 @@ namespace chain {
 struct Dual {
   float v;  // value
   float d;  // tangent d v / d x
+};
+// Run-time constants of a chain: passed to the kernel by value, so chains that differ only in
+// these numbers are the same kernel.  Read by the leaf Arg<I>; the leaf Const<C> is a constant
+// fixed at compile time instead (the built-in chains, and the few values -- 0, +-1, +-2, +-0.5 --
+// whose presence changes what the composer can simplify).
+static constexpr int kMaxArgs = 24;
+struct Args {
+  float c[kMaxArgs];
 };
 // A value that does not depend on x.  Its tangent is identically zero, and carrying that in
 // the TYPE lets the binary operations with a constant operand (Sec. III-A) drop the dead
@@ -69,16 +77,21 @@ __device__ __forceinline__ Dual mul_(Konst a, Dual b) { return Dual{a.v * b.v, a
 __device__ __forceinline__ Dual mul_(Dual a, Konst b) { return Dual{a.v * b.v, a.d * b.v}; }
 __device__ __forceinline__ Konst mul_(Konst a, Konst b) { return Konst{a.v * b.v}; }
 
-// quotient rule: (a/b)' = (a' - (a/b) b') / b
+// quotient rule: (a/b)' = (a' - (a/b) b') / b.  A denominator that has overflowed (an exponential
+// of a large argument: 1/b = 0) drags its tangent to infinity with it, and 0 * inf is NaN where
+// the true derivative tends to 0; the tangent is therefore 0 whenever 1/b is.  (A NaN
+// denominator still gives NaN: NaN == 0 is false.)
 __device__ __forceinline__ Dual div_(Dual a, Dual b) {
   const float r = rcp(b.v);
   const float q = a.v * r;
-  return Dual{q, fma_(-q, b.d, a.d) * r};
+  const float t = fma_(-q, b.d, a.d) * r;
+  return Dual{q, r == 0.0f ? q * 0.0f : t};   // q * 0 keeps a NaN numerator NaN
 }
 __device__ __forceinline__ Dual div_(Konst a, Dual b) {
   const float r = rcp(b.v);
   const float q = a.v * r;
-  return Dual{q, (-q * b.d) * r};
+  const float t = (-q * b.d) * r;
+  return Dual{q, r == 0.0f ? 0.0f : t};
 }
 __device__ __forceinline__ Dual div_(Dual a, Konst b) {
   const float r = rcp(b.v);  // folded at compile time for a literal constant
@@ -87,12 +100,12 @@ __device__ __forceinline__ Dual div_(Dual a, Konst b) {
 __device__ __forceinline__ Konst div_(Konst a, Konst b) { return Konst{a.v * rcp(b.v)}; }
 
 // ---------------------------------------------------------------- leaves
-// Every node has   template <bool kWide> static eval(Dual x)   returning Dual or Konst; kWide
+// Every node has   template <bool kWide> static eval(Dual x, const Args& g)   returning Dual or Konst; kWide
 // says that the result will be stored as fp32 (see the tiers in nfad_math.hpp): a few
 // primitives drop a refinement that only shows at fp32 resolution when it is false.
 struct X {  // the source element, tangent 1
   template <bool kWide>
-  __device__ __forceinline__ static Dual eval(Dual x) {
+  __device__ __forceinline__ static Dual eval(Dual x, const Args&) {
     return x;
   }
 };
@@ -100,22 +113,38 @@ struct X {  // the source element, tangent 1
 template <class C>
 struct Const {
   template <bool kWide>
-  __device__ __forceinline__ static Konst eval(Dual) {
+  __device__ __forceinline__ static Konst eval(Dual, const Args&) {
     return Konst{C::value};
+  }
+};
+// The I-th run-time constant.
+template <int I>
+struct Arg {
+  template <bool kWide>
+  __device__ __forceinline__ static Konst eval(Dual, const Args& g) {
+    return Konst{g.c[I]};
   }
 };
 #define NFAD_CHAIN_CONSTANT(Name, Value) \
   struct Name {                          \
     static constexpr float value = (Value); \
   }
+// The constants that stay compile-time in run-time compiled chains too.
+NFAD_CHAIN_CONSTANT(KZero, 0.0f);
+NFAD_CHAIN_CONSTANT(KOne, 1.0f);
+NFAD_CHAIN_CONSTANT(KMinusOne, -1.0f);
+NFAD_CHAIN_CONSTANT(KTwo, 2.0f);
+NFAD_CHAIN_CONSTANT(KMinusTwo, -2.0f);
+NFAD_CHAIN_CONSTANT(KHalf, 0.5f);
+NFAD_CHAIN_CONSTANT(KMinusHalf, -0.5f);
 
 // ---------------------------------------------------------------- binary, same source
 #define NFAD_CHAIN_BINARY(Name, rule)                                  \
   template <class A, class B>                                          \
   struct Name {                                                        \
     template <bool kWide>                                              \
-    __device__ __forceinline__ static auto eval(Dual x) {              \
-      return rule(A::template eval<kWide>(x), B::template eval<kWide>(x)); \
+    __device__ __forceinline__ static auto eval(Dual x, const Args& g) {              \
+      return rule(A::template eval<kWide>(x, g), B::template eval<kWide>(x, g)); \
     }                                                                  \
   }
 NFAD_CHAIN_BINARY(Add, add_);
@@ -127,16 +156,16 @@ NFAD_CHAIN_BINARY(Div, div_);
 template <class A, class B>
 struct Min {  // the tangent follows the selected operand (the first on a tie)
   template <bool kWide>
-  __device__ __forceinline__ static Dual eval(Dual x) {
-    const Dual a = to_dual(A::template eval<kWide>(x)), b = to_dual(B::template eval<kWide>(x));
+  __device__ __forceinline__ static Dual eval(Dual x, const Args& g) {
+    const Dual a = to_dual(A::template eval<kWide>(x, g)), b = to_dual(B::template eval<kWide>(x, g));
     return a.v <= b.v ? a : (b.v < a.v ? b : Dual{a.v + b.v, a.d + b.d});  // last arm: a NaN stays NaN
   }
 };
 template <class A, class B>
 struct Max {
   template <bool kWide>
-  __device__ __forceinline__ static Dual eval(Dual x) {
-    const Dual a = to_dual(A::template eval<kWide>(x)), b = to_dual(B::template eval<kWide>(x));
+  __device__ __forceinline__ static Dual eval(Dual x, const Args& g) {
+    const Dual a = to_dual(A::template eval<kWide>(x, g)), b = to_dual(B::template eval<kWide>(x, g));
     return a.v >= b.v ? a : (b.v > a.v ? b : Dual{a.v + b.v, a.d + b.d});
   }
 };
@@ -237,8 +266,8 @@ __device__ __forceinline__ Dual tanh_softplus_(Dual a) {
   template <class A>                                                \
   struct Name {                                                     \
     template <bool kWide>                                           \
-    __device__ __forceinline__ static Dual eval(Dual x) {           \
-      return rule(to_dual(A::template eval<kWide>(x)));             \
+    __device__ __forceinline__ static Dual eval(Dual x, const Args& g) {           \
+      return rule(to_dual(A::template eval<kWide>(x, g)));             \
     }                                                               \
   }
 NFAD_CHAIN_UNARY(Relu, relu_);
@@ -257,8 +286,8 @@ NFAD_CHAIN_UNARY(Erf, erf_<kWide>);
 template <class C, class A>
 struct Add<Const<C>, Erf<A>> {
   template <bool kWide>
-  __device__ __forceinline__ static Dual eval(Dual x) {
-    const Dual a = to_dual(A::template eval<kWide>(x));
+  __device__ __forceinline__ static Dual eval(Dual x, const Args& g) {
+    const Dual a = to_dual(A::template eval<kWide>(x, g));
     if constexpr (C::value == 1.0f) return one_plus_erf_<kWide>(a);
     else return add_(Konst{C::value}, erf_<kWide>(a));
   }
@@ -269,8 +298,8 @@ struct Add<Erf<A>, Const<C>> : Add<Const<C>, Erf<A>> {};
 template <class A>
 struct Tanh<Softplus<A>> {
   template <bool kWide>
-  __device__ __forceinline__ static Dual eval(Dual x) {
-    return tanh_softplus_(to_dual(A::template eval<kWide>(x)));
+  __device__ __forceinline__ static Dual eval(Dual x, const Args& g) {
+    return tanh_softplus_(to_dual(A::template eval<kWide>(x, g)));
   }
 };
 
@@ -281,9 +310,10 @@ struct Tanh<Softplus<A>> {
 template <class Chain>
 struct ChainFwdOp {
   static constexpr int kIn = 1, kOut = 2;
+  using Params = chain::Args;   // run-time constants, a by-value kernel argument
   template <bool kWide>
-  __device__ __forceinline__ static void apply(const float (&in)[kIn], float (&out)[kOut]) {
-    const chain::Dual r = chain::to_dual(Chain::template eval<kWide>(chain::seed(in[0])));
+  __device__ __forceinline__ static void apply(const float (&in)[kIn], float (&out)[kOut], const Params& g) {
+    const chain::Dual r = chain::to_dual(Chain::template eval<kWide>(chain::seed(in[0]), g));
     out[0] = r.v;
     out[1] = r.d;
   }
@@ -294,9 +324,10 @@ struct ChainFwdOp {
 template <class... Chains>
 struct ChainFwdMultiOp {
   static constexpr int kIn = 1, kOut = 2 * (int)sizeof...(Chains);
+  using Params = chain::Args;
   template <bool kWide>
-  __device__ __forceinline__ static void apply(const float (&in)[kIn], float (&out)[kOut]) {
-    const chain::Dual r[] = {chain::to_dual(Chains::template eval<kWide>(chain::seed(in[0])))...};
+  __device__ __forceinline__ static void apply(const float (&in)[kIn], float (&out)[kOut], const Params& g) {
+    const chain::Dual r[] = {chain::to_dual(Chains::template eval<kWide>(chain::seed(in[0]), g))...};
 #pragma unroll
     for (int m = 0; m < (int)sizeof...(Chains); ++m) {
       out[2 * m] = r[m].v;

@@ -148,7 +148,7 @@ static int launch_planned(const Ptrs<NIN, NOUT>& p, size_t n, int dtype, LaunchV
 
 template <class Op, typename T, int DTYPE>
 static int launch(const void* const (&in)[Op::kIn], void* const (&out)[Op::kOut], size_t n,
-                  hipStream_t stream) {
+                  hipStream_t stream, const typename OpParams<Op>::type& prm) {
   using P = Ptrs<Op::kIn, Op::kOut>;
   using R = ShapeRule<Op::kIn, Op::kOut, T>;
   P p;
@@ -156,27 +156,27 @@ static int launch(const void* const (&in)[Op::kIn], void* const (&out)[Op::kOut]
   for (int o = 0; o < Op::kOut; ++o) p.out[o] = out[o];
   return launch_planned(
       p, n, DTYPE,
-      [stream](const P& q, size_t m, Geometry g) {
+      [stream, &prm](const P& q, size_t m, Geometry g) {
         if (R::kTwoShapes && g.small)
-          hipLaunchKernelGGL((ew_vec_kernel<Op, T, typename R::Small>), dim3(g.grid), dim3(g.threads), g.lds, stream, q, m);
+          hipLaunchKernelGGL((ew_vec_kernel<Op, T, typename R::Small>), dim3(g.grid), dim3(g.threads), g.lds, stream, q, m, prm);
         else
-          hipLaunchKernelGGL((ew_vec_kernel<Op, T, typename R::Large>), dim3(g.grid), dim3(g.threads), g.lds, stream, q, m);
+          hipLaunchKernelGGL((ew_vec_kernel<Op, T, typename R::Large>), dim3(g.grid), dim3(g.threads), g.lds, stream, q, m, prm);
         return hipGetLastError();
       },
-      [stream](const P& q, size_t m, Geometry g) {
-        hipLaunchKernelGGL((ew_scalar_kernel<Op, T>), dim3(g.grid), dim3(g.threads), 0, stream, q, m);
+      [stream, &prm](const P& q, size_t m, Geometry g) {
+        hipLaunchKernelGGL((ew_scalar_kernel<Op, T>), dim3(g.grid), dim3(g.threads), 0, stream, q, m, prm);
         return hipGetLastError();
       });
 }
 
 template <class Op>
 static int launch_dtype(int dtype, const void* const (&in)[Op::kIn], void* const (&out)[Op::kOut],
-                        size_t n, void* stream) {
+                        size_t n, void* stream, const typename OpParams<Op>::type& prm) {
   hipStream_t s = reinterpret_cast<hipStream_t>(stream);
   switch (dtype) {
-    case NFAD_F32: return launch<Op, float, NFAD_F32>(in, out, n, s);
-    case NFAD_F16: return launch<Op, _Float16, NFAD_F16>(in, out, n, s);
-    case NFAD_BF16: return launch<Op, __bf16, NFAD_BF16>(in, out, n, s);
+    case NFAD_F32: return launch<Op, float, NFAD_F32>(in, out, n, s, prm);
+    case NFAD_F16: return launch<Op, _Float16, NFAD_F16>(in, out, n, s, prm);
+    case NFAD_BF16: return launch<Op, __bf16, NFAD_BF16>(in, out, n, s, prm);
   }
   return NFAD_EINVAL_DTYPE;
 }
@@ -206,10 +206,10 @@ static int validate(const void* const (&in)[NIN], void* const (&out)[NOUT], size
 
 template <class Op>
 static int run(int dtype, const void* const (&in)[Op::kIn], void* const (&out)[Op::kOut], size_t n,
-               void* stream) {
+               void* stream, const typename OpParams<Op>::type& prm = typename OpParams<Op>::type{}) {
   const int rc = validate<Op::kIn, Op::kOut>(in, out, n, dtype);
   if (rc != NFAD_OK || n == 0) return rc;
-  return launch_dtype<Op>(dtype, in, out, n, stream);
+  return launch_dtype<Op>(dtype, in, out, n, stream, prm);
 }
 
 }  // namespace nfad

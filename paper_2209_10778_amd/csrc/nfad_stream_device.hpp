@@ -114,6 +114,31 @@ struct Ptrs {
   void* out[NOUT];
 };
 
+// An operation may take a block of run-time parameters (a by-value kernel argument): it then
+// declares `using Params = ...` and its apply() takes the block as a third argument.  The others
+// get an empty block.
+struct NoParams {};
+template <class...>
+struct VoidType {
+  using type = void;
+};
+template <class Op, class = void>
+struct OpParams {
+  using type = NoParams;
+  template <bool kWide>
+  __device__ __forceinline__ static void apply(const float (&in)[Op::kIn], float (&out)[Op::kOut], const type&) {
+    Op::template apply<kWide>(in, out);
+  }
+};
+template <class Op>
+struct OpParams<Op, typename VoidType<typename Op::Params>::type> {
+  using type = typename Op::Params;
+  template <bool kWide>
+  __device__ __forceinline__ static void apply(const float (&in)[Op::kIn], float (&out)[Op::kOut], const type& prm) {
+    Op::template apply<kWide>(in, out, prm);
+  }
+};
+
 static constexpr int kScalarThreads = 256;
 
 // 16-byte vector body.  Requires every pointer 16-byte aligned.  Tile = kThreads * kUnroll
@@ -123,7 +148,8 @@ static constexpr int kScalarThreads = 256;
 // block.  The kernel uses no LDS: the dynamic LDS size of the launch only limits how many
 // blocks fit on a compute unit.
 template <class Op, typename T, class Sh>
-__global__ __launch_bounds__((Sh::kThreads)) void ew_vec_kernel(Ptrs<Op::kIn, Op::kOut> p, size_t n) {
+__global__ __launch_bounds__((Sh::kThreads)) void ew_vec_kernel(Ptrs<Op::kIn, Op::kOut> p, size_t n,
+                                                                typename OpParams<Op>::type prm) {
   using S = Storage<T>;
   using Vec = typename S::Vec;
   constexpr int kVec = S::kVec;
@@ -151,7 +177,7 @@ __global__ __launch_bounds__((Sh::kThreads)) void ew_vec_kernel(Ptrs<Op::kIn, Op
         float fin[Op::kIn], fout[Op::kOut];
 #pragma unroll
         for (int i = 0; i < Op::kIn; ++i) fin[i] = S::up(vin[j][i][e]);
-        Op::template apply<kWide>(fin, fout);
+        OpParams<Op>::template apply<kWide>(fin, fout, prm);
 #pragma unroll
         for (int o = 0; o < Op::kOut; ++o) vout[o][e] = S::down(fout[o]);
       }
@@ -177,7 +203,7 @@ __global__ __launch_bounds__((Sh::kThreads)) void ew_vec_kernel(Ptrs<Op::kIn, Op
         float fin[Op::kIn], fout[Op::kOut];
 #pragma unroll
         for (int i = 0; i < Op::kIn; ++i) fin[i] = S::up(vin[i][e]);
-        Op::template apply<kWide>(fin, fout);
+        OpParams<Op>::template apply<kWide>(fin, fout, prm);
 #pragma unroll
         for (int o = 0; o < Op::kOut; ++o) vout[o][e] = S::down(fout[o]);
       }
@@ -189,7 +215,7 @@ __global__ __launch_bounds__((Sh::kThreads)) void ew_vec_kernel(Ptrs<Op::kIn, Op
       float fin[Op::kIn], fout[Op::kOut];
 #pragma unroll
       for (int i = 0; i < Op::kIn; ++i) fin[i] = S::up(reinterpret_cast<const T*>(p.in[i])[k]);
-      Op::template apply<kWide>(fin, fout);
+      OpParams<Op>::template apply<kWide>(fin, fout, prm);
 #pragma unroll
       for (int o = 0; o < Op::kOut; ++o) reinterpret_cast<T*>(p.out[o])[k] = S::down(fout[o]);
     }
@@ -199,7 +225,8 @@ __global__ __launch_bounds__((Sh::kThreads)) void ew_vec_kernel(Ptrs<Op::kIn, Op
 // Element-at-a-time kernel for pointers that are not all 16-byte aligned: same values,
 // lower bandwidth.
 template <class Op, typename T>
-__global__ __launch_bounds__(kScalarThreads) void ew_scalar_kernel(Ptrs<Op::kIn, Op::kOut> p, size_t n) {
+__global__ __launch_bounds__(kScalarThreads) void ew_scalar_kernel(Ptrs<Op::kIn, Op::kOut> p, size_t n,
+                                                                   typename OpParams<Op>::type prm) {
   using S = Storage<T>;
   constexpr bool kWide = sizeof(T) == 4;
   const size_t stride = (size_t)gridDim.x * kScalarThreads;
@@ -207,7 +234,7 @@ __global__ __launch_bounds__(kScalarThreads) void ew_scalar_kernel(Ptrs<Op::kIn,
     float fin[Op::kIn], fout[Op::kOut];
 #pragma unroll
     for (int i = 0; i < Op::kIn; ++i) fin[i] = S::up(reinterpret_cast<const T*>(p.in[i])[k]);
-    Op::template apply<kWide>(fin, fout);
+    OpParams<Op>::template apply<kWide>(fin, fout, prm);
 #pragma unroll
     for (int o = 0; o < Op::kOut; ++o) reinterpret_cast<T*>(p.out[o])[k] = S::down(fout[o]);
   }

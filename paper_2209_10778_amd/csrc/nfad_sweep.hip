@@ -250,10 +250,10 @@ template <class Op, typename T, int THREADS, int UNROLL>
 static hipError_t launch_op_tu(bool ntl, const Ptrs<Op::kIn, Op::kOut>& p, size_t n, Launch l) {
   if (ntl)
     hipLaunchKernelGGL((ew_vec_kernel<Op, T, Shape<THREADS, UNROLL, true>>), dim3(l.grid), dim3(THREADS), l.lds,
-                       l.stream, p, n);
+                       l.stream, p, n, NoParams{});
   else
     hipLaunchKernelGGL((ew_vec_kernel<Op, T, Shape<THREADS, UNROLL, false>>), dim3(l.grid), dim3(THREADS), l.lds,
-                       l.stream, p, n);
+                       l.stream, p, n, NoParams{});
   return hipGetLastError();
 }
 template <class Op, typename T>

@@ -4,10 +4,14 @@
  *
  * For each activation (Table I of the paper + the erf form of GELU) and each storage type
  * that C can hold natively (fp32), on n seeded pseudo-random inputs with a ragged n:
- *   fused forward   y = f(x), dydx = f'(x)           (Sec. II-C eq. 3)   max-abs 2e-6
- *   backward        gx = gy * dydx                    (Sec. II-C eq. 4)   <= 1 fp32 ulp of the exact product
- *   recomputation and save-all baselines                                  same bars
- * plus the error paths that need no launch.  Exit status 0 = all checks passed. */
+ *   fused forward   y = f(x), dydx = f'(x)           (Sec. II-C eq. 3)
+ *   backward        gx = gy * dydx                    (Sec. II-C eq. 4)
+ *   recomputation and save-all baselines
+ * every result against max(2e-6, one fp32 ulp of the reference) -- with |x| <= 6 that is the flat
+ * 2e-6 wherever the reference is below 16 -- plus the error paths that need no launch.
+ * Backward passes consume the ORACLE's forward results rounded to fp32 (uploaded from the host),
+ * on the GPU and in the oracle alike: no oracle input comes from the GPU.
+ * Exit status 0 = all checks passed. */
 #define __HIP_PLATFORM_AMD__ 1
 #include <hip/hip_runtime_api.h>
 #include <math.h>
@@ -54,23 +58,22 @@ static double uniform01(void) { /* splitmix64 */
 }
 
 static int g_failures = 0;
-static void check(const char* what, int kind, const float* got, const double* ref, size_t n, double tol_abs,
-                  int tol_ulp) {
-  double worst = 0.0;
+/* |got - ref| <= max(2e-6, ulp_f32(ref)) + allowance[i] (allowance may be NULL) */
+static void check(const char* what, int kind, const float* got, const double* ref, size_t n, const double* allowance) {
+  double worst = 0.0, worst_over_bar = 0.0;
   size_t at = 0, bad = 0;
   for (size_t i = 0; i < n; ++i) {
     const double err = fabs((double)got[i] - ref[i]);
-    double tol = tol_abs;
-    if (tol_ulp) { /* one fp32 ulp of the reference */
-      int e;
-      frexp(ref[i], &e);
-      const double ulp = ldexp(1.0, (e - 1 < -126 ? -126 : e - 1) - 23);
-      if (ulp * tol_ulp > tol) tol = ulp * tol_ulp;
-    }
-    if (!(err <= tol)) ++bad;
+    int e;
+    frexp(ref[i], &e);
+    const double ulp = ldexp(1.0, (e - 1 < -126 ? -126 : e - 1) - 23);
+    const double bar = ulp > 2e-6 ? ulp : 2e-6;
+    if (!(err <= bar + (allowance ? allowance[i] : 0.0))) ++bad;
     if (err > worst || err != err) { worst = err; at = i; }
+    if (err / bar > worst_over_bar) worst_over_bar = err / bar;
   }
-  printf("  %-22s kind %d  max |err| %.3e at %zu  %s\n", what, kind, worst, at, bad ? "FAIL" : "ok");
+  printf("  %-22s kind %d  max |err| %.3e at %zu (%.3f of the bar)  %s\n", what, kind, worst, at, worst_over_bar,
+         bad ? "FAIL" : "ok");
   if (bad) ++g_failures;
 }
 
@@ -104,19 +107,21 @@ int main(void) {
   HIP_OK(hipStreamCreate(&stream));
 
   for (int kind = 0; kind < 4; ++kind) {
-    /* the method: fused forward, then backward on the tangent the forward stored */
+    /* the method: fused forward; then backward on the ORACLE's tangent rounded to fp32 */
     NFAD_OK_(nfad_fwd(kind, dx, dy, dd, n, NFAD_F32, stream));
-    NFAD_OK_(nfad_bwd(dgy, dd, dgx, n, NFAD_F32, stream));
     HIP_OK(hipStreamSynchronize(stream));
     nfad_oracle_fwd(kind, x64, y64, d64, n, 1);
     HIP_OK(hipMemcpy(hout, dy, bytes, hipMemcpyDeviceToHost));
-    check("nfad_fwd y", kind, hout, y64, n, 2e-6, 0);
+    check("nfad_fwd y", kind, hout, y64, n, NULL);
     HIP_OK(hipMemcpy(hout, dd, bytes, hipMemcpyDeviceToHost));
-    check("nfad_fwd dydx", kind, hout, d64, n, 2e-6, 0);
-    for (size_t i = 0; i < n; ++i) dst64[i] = hout[i]; /* the stored tangent, exactly */
+    check("nfad_fwd dydx", kind, hout, d64, n, NULL);
+    for (size_t i = 0; i < n; ++i) { hout2[i] = (float)d64[i]; dst64[i] = hout2[i]; } /* stored tangent of record */
+    HIP_OK(hipMemcpy(dd, hout2, bytes, hipMemcpyHostToDevice));
+    NFAD_OK_(nfad_bwd(dgy, dd, dgx, n, NFAD_F32, stream));
+    HIP_OK(hipStreamSynchronize(stream));
     nfad_oracle_bwd(gy64, dst64, gx64, n, 1);
     HIP_OK(hipMemcpy(hout2, dgx, bytes, hipMemcpyDeviceToHost));
-    check("nfad_bwd gx", kind, hout2, gx64, n, 0.0, 1);
+    check("nfad_bwd gx", kind, hout2, gx64, n, NULL);
 
     /* recomputation baseline */
     NFAD_OK_(nfad_recompute_fwd(kind, dx, dy, n, NFAD_F32, stream));
@@ -125,9 +130,9 @@ int main(void) {
     nfad_oracle_recompute_fwd(kind, x64, y64, n, 1);
     nfad_oracle_recompute_bwd(kind, gy64, x64, gx64, n, 1);
     HIP_OK(hipMemcpy(hout, dy, bytes, hipMemcpyDeviceToHost));
-    check("recompute_fwd y", kind, hout, y64, n, 2e-6, 0);
+    check("recompute_fwd y", kind, hout, y64, n, NULL);
     HIP_OK(hipMemcpy(hout, dgx, bytes, hipMemcpyDeviceToHost));
-    check("recompute_bwd gx", kind, hout, gx64, n, 2e-6, 2);
+    check("recompute_bwd gx", kind, hout, gx64, n, NULL);
 
     /* save-all baseline: the library and the oracle must agree on the number of saved tensors */
     const int k = nfad_saveall_num_saved(kind);
@@ -140,22 +145,25 @@ int main(void) {
     saved[0] = dx; /* stands for x, not written */
     for (int j = 1; j < k; ++j) saved[j] = dsv[j];
     NFAD_OK_(nfad_saveall_fwd(kind, dx, dy, saved, n, NFAD_F32, stream));
-    NFAD_OK_(nfad_saveall_bwd(kind, dgy, (const void* const*)saved, dgx, n, NFAD_F32, stream));
     HIP_OK(hipStreamSynchronize(stream));
     nfad_oracle_saveall_fwd(kind, x64, y64, sv64, n, 1);
     HIP_OK(hipMemcpy(hout, dy, bytes, hipMemcpyDeviceToHost));
-    check("saveall_fwd y", kind, hout, y64, n, 2e-6, 0);
+    check("saveall_fwd y", kind, hout, y64, n, NULL);
     for (int j = 1; j < k; ++j) {
       char what[32];
       snprintf(what, sizeof what, "saveall_fwd saved[%d]", j);
       HIP_OK(hipMemcpy(hout, dsv[j], bytes, hipMemcpyDeviceToHost));
-      check(what, kind, hout, sv64[j], n, 2e-6, 2);
-      for (size_t i = 0; i < n; ++i) sv64[j][i] = hout[i]; /* backward reads what forward stored */
+      check(what, kind, hout, sv64[j], n, NULL);
+      /* backward reads the ORACLE's intermediates rounded to fp32, on both sides */
+      for (size_t i = 0; i < n; ++i) { hout[i] = (float)sv64[j][i]; sv64[j][i] = hout[i]; }
+      HIP_OK(hipMemcpy(dsv[j], hout, bytes, hipMemcpyHostToDevice));
     }
     memcpy(sv64[0], x64, n * 8);
+    NFAD_OK_(nfad_saveall_bwd(kind, dgy, (const void* const*)saved, dgx, n, NFAD_F32, stream));
+    HIP_OK(hipStreamSynchronize(stream));
     nfad_oracle_saveall_bwd(kind, gy64, (const double* const*)sv64, gx64, n, 1);
     HIP_OK(hipMemcpy(hout, dgx, bytes, hipMemcpyDeviceToHost));
-    check("saveall_bwd gx", kind, hout, gx64, n, 4e-6, 4);
+    check("saveall_bwd gx", kind, hout, gx64, n, NULL);
   }
 
   /* error paths: validation happens before any launch */
@@ -171,10 +179,15 @@ int main(void) {
   NFAD_OK_(nfad_chain_fwd(id, dx, dy, dd, n, NFAD_F32, stream));
   HIP_OK(hipStreamSynchronize(stream));
   nfad_oracle_fwd(NFAD_MISH, x64, y64, d64, n, 1);
+  /* a composed chain: the bar plus 5e-7 * max(1,|x|) * max(1,|ref|) (a dozen fp32 primitives) */
+  double* allow = malloc(n * 8);
+  for (size_t i = 0; i < n; ++i) allow[i] = 5e-7 * fmax(1.0, fabs(x64[i])) * fmax(1.0, fabs(y64[i]));
   HIP_OK(hipMemcpy(hout, dy, bytes, hipMemcpyDeviceToHost));
-  check("chain(mish) y", NFAD_MISH, hout, y64, n, 4e-6, 2);
+  check("chain(mish) y", NFAD_MISH, hout, y64, n, allow);
+  for (size_t i = 0; i < n; ++i) allow[i] = 5e-7 * fmax(1.0, fabs(x64[i])) * fmax(1.0, fabs(d64[i]));
   HIP_OK(hipMemcpy(hout, dd, bytes, hipMemcpyDeviceToHost));
-  check("chain(mish) dydx", NFAD_MISH, hout, d64, n, 4e-6, 2);
+  check("chain(mish) dydx", NFAD_MISH, hout, d64, n, allow);
+  free(allow);
   NFAD_OK_(nfad_chain_release(id));
 
   HIP_OK(hipStreamDestroy(stream));

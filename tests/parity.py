@@ -4,7 +4,18 @@ Bar (fp32 math, one rounding to storage):
   f32 storage : |gpu - ref| <= max(2e-6, ulp_f32(ref))      (2e-6 flat wherever |ref| < 16)
   f16 / bf16  : |gpu - ref| <= max(ulp_T(ref), 2e-6)
 with ulp_T(v) = 2^(max(floor(log2 |v|), e_min) - p), (p, e_min) = (23,-126) f32, (10,-14) f16,
-(7,-126) bf16, and ref the fp64 oracle value on the storage-rounded input.
+(7,-126) bf16, and ref the fp64 oracle value on the storage-rounded input.  Every pass of the
+method and of the two baselines is gated at exactly this bar (`compare` with no allowance).
+
+Two derived budgets exist, for results the bar was not written for:
+  * a gradient computed from a tangent that was itself rounded to storage by the GPU (forward
+    feeding backward): the tangent may be off by its own bar, which the upstream gradient
+    scales, and the product is rounded once more: |gy| * bar_T(dydx) + bar_T(gx)
+    (`two_stage_budget`);
+  * a composed chain of up to a dozen fp32 primitives: each primitive rounds (2^-24 relative)
+    and the hardware exponential's argument rounding grows with |x|, so on top of the bar
+    5e-7 * max(1, |x|) * max(1, |ref|) (`chain_allowance`; eight roundings of a value of
+    magnitude max(1, |ref|) are 4.8e-7 relative).
 """
 from __future__ import annotations
 
@@ -28,6 +39,21 @@ def tolerance(ref: torch.Tensor, dtype: torch.dtype) -> torch.Tensor:
     return torch.clamp(ulp_of(ref, dtype), min=ABS_FLOOR)
 
 
+def chain_allowance(x64, ref64):
+    """Allowance on top of the bar for a composed chain (see the module docstring); numpy float64."""
+    return 5e-7 * np.maximum(1.0, np.abs(np.asarray(x64))) * np.maximum(1.0, np.abs(np.asarray(ref64)))
+
+
+def two_stage_budget(gy64, d_ref64, gx_ref64, dtype: torch.dtype, d_allowance=None):
+    """Tolerance (numpy float64) of gx = gy * dydx when dydx is the GPU's own stored tangent:
+    |gy| * (bar_T(dydx) [+ allowance of dydx]) for the tangent's error; subtract the plain bar
+    that `compare` applies itself, i.e. pass the result as `extra_tol`."""
+    tol_d = tolerance(torch.as_tensor(np.asarray(d_ref64), dtype=torch.float64), dtype).numpy()
+    if d_allowance is not None:
+        tol_d = tol_d + np.asarray(d_allowance)
+    return np.abs(np.asarray(gy64)) * tol_d
+
+
 def compare(got: torch.Tensor, ref64, dtype: torch.dtype, what: str = "", flat_abs: float | None = None,
             extra_tol=None):
     """Element-by-element check of a storage tensor against float64 reference values.
@@ -46,11 +72,13 @@ def compare(got: torch.Tensor, ref64, dtype: torch.dtype, what: str = "", flat_a
         tol = tol + torch.as_tensor(np.asarray(extra_tol), dtype=torch.float64).reshape(-1).to(dev)
     bad = err > tol
     ulps = err / ulp_of(ref, dtype)
+    bar = tolerance(ref, dtype) if flat_abs is None else torch.full_like(ref, flat_abs)
     stats = {
         "n": int(g.numel()),
         "max_abs": float(err.max()),
         "max_ulp": float(ulps.max()),                 # strict statistic, reported not gated
         "n_over_1ulp": int((ulps > 1.0).sum()),
+        "max_over_bar": float((err / bar).max()),     # worst error in units of the stated bar (no allowance)
     }
     if bool(bad.any()):
         i = int(torch.argmax(err / tol))

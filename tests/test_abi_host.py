@@ -25,7 +25,7 @@ def test_header_declares_the_expected_entry_points():
         "nfad_saveall_fwd", "nfad_saveall_bwd", "nfad_status_string", "nfad_version",
         "nfad_chain_count", "nfad_chain_name", "nfad_chain_program", "nfad_chain_fwd",
         "nfad_chain_compile", "nfad_chain_release", "nfad_chain_log", "nfad_chain_compile_multi",
-        "nfad_chain_num_outputs", "nfad_chain_fwd_multi", "nfad_bwd_multi"])
+        "nfad_chain_num_outputs", "nfad_chain_fwd_multi", "nfad_bwd_multi", "nfad_chain_kernel"])
 
 
 def test_library_exports_every_declared_symbol():

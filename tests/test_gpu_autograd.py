@@ -8,7 +8,7 @@ from oracle import chain as ochain
 import paper_2209_10778_amd as nfad
 from paper_2209_10778_amd import autograd as A
 from paper_2209_10778_amd import inputs
-from parity import compare, tolerance
+from parity import chain_allowance, compare, two_stage_budget
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -30,8 +30,11 @@ def test_value_and_gradient(name, mode):
     y.backward(gy.to(DEV).view(shape))
     compare(y.detach(), y_ref, torch.float32, f"{name} {mode} y")
     g_ref = gy64 * d_ref
-    tol = np.abs(gy64) * 4e-6 * np.maximum(1.0, np.abs(x64))
-    compare(xd.grad, g_ref, torch.float32, f"{name} {mode} grad", extra_tol=tol)
+    # fad: the GPU's own stored tangent feeds the product (two-stage budget); the two baselines
+    # compute gy * f'(x) in one kernel (the stated bar, no allowance)
+    extra = two_stage_budget(gy64, d_ref, g_ref, torch.float32) if mode == "fad" else None
+    st = compare(xd.grad, g_ref, torch.float32, f"{name} {mode} grad", extra_tol=extra)
+    print(f"\n[autograd {name} {mode}] grad err / stated bar {st['max_over_bar']:.3f}")
 
 
 def test_only_one_tensor_is_saved_by_fad():
@@ -57,9 +60,8 @@ def test_chain_front_end_builtin_and_compiled():
         y = A.chain(xd, spec)
         y.sum().backward()
         y_ref, d_ref = ochain.eval_chain(prog, x64)
-        rel = 2e-6 * np.maximum(1.0, np.abs(x64))
-        compare(y.detach(), y_ref, torch.float32, f"chain {spec} y", extra_tol=rel * np.maximum(1, np.abs(y_ref)))
-        compare(xd.grad, d_ref, torch.float32, f"chain {spec} grad", extra_tol=rel * np.maximum(1, np.abs(d_ref)))
+        compare(y.detach(), y_ref, torch.float32, f"chain {spec} y", extra_tol=chain_allowance(x64, y_ref))
+        compare(xd.grad, d_ref, torch.float32, f"chain {spec} grad", extra_tol=chain_allowance(x64, d_ref))
 
 
 def test_module_in_a_small_network_trains_a_step():
@@ -95,8 +97,8 @@ def test_non_contiguous_and_16bit_inputs(dtype):
     g_ref = gy64 * d_ref
     assert xd.grad.shape == xd.shape
     # two roundings (dydx, then the product), scaled by |gy|
-    tol = np.abs(gy64) * tolerance(torch.from_numpy(d_ref), td).numpy()
-    compare(xd.grad.contiguous(), g_ref, td, f"non-contiguous grad {dtype}", extra_tol=tol)
+    compare(xd.grad.contiguous(), g_ref, td, f"non-contiguous grad {dtype}",
+            extra_tol=two_stage_budget(gy64, d_ref, g_ref, td))
 
 
 def test_compiled_chain_cache_is_bounded(monkeypatch):
@@ -114,7 +116,9 @@ def test_compiled_chain_cache_is_bounded(monkeypatch):
         ids.append(A._compiled[prog])
         assert torch.allclose(y, torch.tanh(x * (1.5 + k)) * x, rtol=1e-5, atol=1e-6)
     assert len(A._compiled) <= A.MAX_COMPILED
-    assert all(nfad.nfad_chain_name(i) is None for i in ids[:3])        # evicted and released
-    assert all(nfad.nfad_chain_name(i) is not None for i in ids[3:])    # still live
-    y = A.chain(x, "x 1.5 * tanh x *")                                  # an evicted program compiles again
+    live = set(A._compiled.values())
+    assert len(live) == 3 and all(nfad.nfad_chain_name(i) is not None for i in live)
+    assert len(set(ids)) < len(ids)                                     # released ids were handed out again
+    assert len({nfad.nfad_chain_kernel(i) for i in live}) == 1          # one kernel serves every constant
+    y = A.chain(x, "x 1.5 * tanh x *")                                  # an evicted program is accepted again
     assert torch.allclose(y, torch.tanh(x * 1.5) * x, rtol=1e-5, atol=1e-6)

@@ -8,7 +8,7 @@ import torch
 import oracle
 import paper_2209_10778_amd as nfad
 from paper_2209_10778_amd import inputs
-from parity import compare, tolerance
+from parity import compare, two_stage_budget
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -40,35 +40,32 @@ def _fwd_bwd_case(cfg, spec, kind, dtype, flat_abs=None, baselines=False):
     print(f"  y {sy}\n  dydx {sd}\n  gx {sg}", flush=True)
 
     # end to end (GPU fwd feeding GPU bwd): finite everywhere, and within the two-rounding budget
+    # (fp32 on unit-variance inputs: within the flat bar itself)
     nfad.nfad_bwd(gyd, d, gx)
-    assert bool(torch.isfinite(gx.float()).all())
-    g_e2e = torch.from_numpy(oracle.bwd(gy64, d_ref)).to(DEV)
-    err = (gx.double() - g_e2e).abs()
-    budget = gyd.double().abs() * tolerance(torch.from_numpy(d_ref).to(DEV), td) + tolerance(g_e2e, td)
-    assert bool((err <= budget).all()), f"{tag}: end-to-end gx out of budget"
-    del err, budget, g_e2e
+    g_e2e = oracle.bwd(gy64, d_ref)
+    se = compare(gx, g_e2e, td, f"{tag} end-to-end gx", flat_abs=flat_abs,
+                 extra_tol=None if flat_abs is not None else two_stage_budget(gy64, d_ref, g_e2e, td))
+    print(f"  end-to-end gx {se}", flush=True)
+    del g_e2e
 
     if baselines:
         k = nfad.nfad_saveall_num_saved(kind)
         yb = torch.empty_like(xd)
         nfad.nfad_recompute_fwd(kind, xd, yb)
-        compare(yb, y_ref, td, f"{tag} recompute y")
+        compare(yb, y_ref, td, f"{tag} recompute y", flat_abs=flat_abs)
         nfad.nfad_recompute_bwd(kind, gyd, xd, gx)
-        rb_ref = oracle.recompute_bwd(kind, gy64, x64)
-        rb_tol = np.abs(gy64) * tolerance(torch.from_numpy(d_ref), torch.float32).numpy() \
-            + tolerance(torch.from_numpy(rb_ref), td).numpy()
-        assert np.all(np.abs(gx.double().cpu().numpy() - rb_ref) <= rb_tol), f"{tag}: recompute gx"
+        sr = compare(gx, oracle.recompute_bwd(kind, gy64, x64), td, f"{tag} recompute gx", flat_abs=flat_abs)
         y_sa, saved_ref = oracle.saveall_fwd(kind, x64)
         saved = [xd] + [torch.empty_like(xd) for _ in range(k - 1)]
         nfad.nfad_saveall_fwd(kind, xd, yb, saved)
-        compare(yb, y_sa, td, f"{tag} saveall y")
+        compare(yb, y_sa, td, f"{tag} saveall y", flat_abs=flat_abs)
         for j in range(1, k):
-            compare(saved[j], saved_ref[j], td, f"{tag} saveall saved[{j}]")
+            compare(saved[j], saved_ref[j], td, f"{tag} saveall saved[{j}]", flat_abs=flat_abs)
         saved_st = [x] + [inputs.to_storage(s.astype(np.float32), dtype) for s in saved_ref[1:]]
         sb_ref = oracle.saveall_bwd(kind, gy64, [inputs.storage_to_f64(s) for s in saved_st])
         nfad.nfad_saveall_bwd(kind, gyd, [s.to(DEV) for s in saved_st], gx)
-        sb_tol = tolerance(torch.from_numpy(sb_ref), td).numpy() + np.abs(gy64) * 4e-6 * np.maximum(1.0, np.abs(x64))
-        assert np.all(np.abs(gx.double().cpu().numpy() - sb_ref) <= sb_tol), f"{tag}: saveall gx"
+        ss = compare(gx, sb_ref, td, f"{tag} saveall gx", flat_abs=flat_abs)
+        print(f"  recompute gx {sr}\n  saveall gx {ss}", flush=True)
     torch.cuda.synchronize()
     del xd, gyd, y, d, gx
     torch.cuda.empty_cache()
