@@ -18,7 +18,17 @@ dydx; backward is one multiply.  Intermediates never exist, so there is nothing 
 
 A binary operator is fad only if both operands derive from the same source tensor, or one
 of them is a Python number (Sec. III-A); otherwise it is an nfad operator and ends the chain.
-A lazy tensor used by several consumers is materialised once per distinct chain (M outputs).
+One source, several outputs (R^1 -> R^M, Sec. IV-A/IV-B): when a chain ends, every other chain
+over the same source that has been recorded but not yet consumed is fused into the SAME kernel
+(x is read once; one value and one saved tangent per output; the backward pass merges the
+upstream gradients in one kernel).
+
+Eager semantics under mutation: an in-place operator (or out=) that writes a tensor first
+resolves every recorded chain over that tensor, so deferred chains never see a later value of
+their source; a tensor that has been resolved counts as an ordinary tensor from then on (an
+in-place operator on it cannot leave a stale program behind); and a source changed behind the
+detector's back (after the context has closed, or through a view) is caught by its version
+counter when the chain is resolved.
 
 A chain of ONE plain primitive (NY directly followed by YN; Sec. IV-B "Efficiency" treats this
 case specially too) is not fused: the primitive runs natively, because its own backward keeps
@@ -35,6 +45,7 @@ fused kernel would add a saved tangent.  Single calls of the framework's fused a
 from __future__ import annotations
 
 import math
+import weakref
 from typing import List, Optional
 
 import torch
@@ -60,19 +71,34 @@ class Lazy(torch.Tensor):
                                                 requires_grad=source.requires_grad)
         r._source, r._program, r._tracer, r._value = source, list(program), tracer, None
         r._nops, r._native = nops, native      # operators recorded; (func, args, kwargs) of a lone primitive
+        r._source_version = source._version    # the chain means f(source as it is NOW)
+        r._extended = False                    # True once another recorded chain continues this one
+        tracer._register(r)
         return r
 
     def materialize(self) -> torch.Tensor:
         """YN: run the fused forward kernel of the recorded chain; keeps only dydx for backward.
-        A chain of one plain primitive runs that primitive natively instead."""
+        A chain of one plain primitive runs that primitive natively instead.  Chains over the same
+        source that are waiting to be consumed are resolved by the same kernel."""
         if self._value is None:
+            if self._source._version != self._source_version:
+                raise RuntimeError(
+                    "a tensor was modified in place after a forward-AD chain over it was recorded and before the "
+                    "chain was used; resolve the chain first (use its result), or do not modify its source")
             if self._nops == 1 and self._native is not None:
                 func, args, kwargs = self._native
-                self._value = func(*args, **kwargs)
+                with torch._C.DisableTorchFunction():      # the primitive itself, not another recording
+                    self._value = func(*args, **kwargs)
                 self._tracer.native_singles += 1
             else:
-                self._value = A.chain(self._source, " ".join(self._program))
-                self._tracer.kernels.append(" ".join(self._program))
+                group = self._tracer._siblings(self)
+                programs = [" ".join(l._program) for l in group]
+                if len(group) == 1:
+                    self._value = A.chain(self._source, programs[0])
+                else:
+                    for l, v in zip(group, A.chain_multi(self._source, programs)):
+                        l._value, l._native = v, None
+                self._tracer.kernels.append(" ; ".join(programs))
             self._native = None
         return self._value
 
@@ -87,8 +113,17 @@ class Lazy(torch.Tensor):
     @classmethod
     def __torch_function__(cls, func, types, args=(), kwargs=None):
         kwargs = kwargs or {}
-        lazies = [a for a in _flatten(args) + _flatten(tuple(kwargs.values())) if isinstance(a, Lazy)]
-        return lazies[0]._tracer._dispatch(func, args, kwargs)
+        for a in args:
+            if type(a) is Lazy:
+                tracer = a._tracer
+                break
+        else:
+            tracer = [a for a in _flatten(args) + _flatten(tuple(kwargs.values())) if isinstance(a, Lazy)][0]._tracer
+        if not kwargs:
+            r = tracer._fast(func, args)
+            if r is not _MISS:
+                return r
+        return tracer._dispatch(func, args, kwargs)
 
 
 def _flatten(xs):
@@ -167,6 +202,28 @@ def _op_name(func):
     return _OP_TABLE.get(getattr(func, "__name__", ""))
 
 
+_MISS = object()
+_X = ["x"]
+# function object -> (kind, token, operands swapped, is a fad operator of any sort, may write in place);
+# kind 1: plain unary primitive, 2: plain binary arithmetic, 0: neither
+_FUNC_KIND = {}
+_PLAIN_UNARY = {"neg": "neg", "exp": "exp", "log": "log", "tanh": "tanh", "sigmoid": "sigmoid", "erf": "erf",
+                "relu": "relu", "abs": "abs", "sqrt": "sqrt"}
+_PLAIN_BINARY = {"add": ("+", False), "radd": ("+", False), "sub": ("-", False), "rsub": ("-", True),
+                 "mul": ("*", False), "rmul": ("*", False), "div": ("/", False), "rdiv": ("/", True)}
+
+
+def _kind_of(func):
+    name = getattr(func, "__name__", "")
+    op = _OP_TABLE.get(name)
+    writes = (name.endswith("_") and not name.endswith("__")) or name in _INPLACE_DUNDERS
+    if op in _PLAIN_UNARY:
+        return (1, _PLAIN_UNARY[op], False, True, writes)
+    if op in _PLAIN_BINARY:
+        return (2,) + _PLAIN_BINARY[op] + (True, writes)
+    return (0, None, False, op is not None, writes)
+
+
 class fuse(TorchFunctionMode):
     """Context manager: detect fad chains and run each as one fused kernel."""
 
@@ -174,8 +231,52 @@ class fuse(TorchFunctionMode):
         super().__init__()
         self.require_cuda = require_cuda   # False only lets chains be RECORDED on host tensors (tests)
         self.states: List[str] = []      # forward state of every tensor-operator pair seen
-        self.kernels: List[str] = []     # chain programs that were materialised, in order
+        self.kernels: List[str] = []     # chain programs that were materialised, in order (" ; " joins a fused group)
         self.native_singles = 0          # one-primitive chains that were run natively instead
+        self._pending = {}               # id(source) -> weak references to the chains recorded over it
+
+    # ---- chains waiting to be consumed, per source
+    def _register(self, lazy):
+        key = id(lazy._source)
+        refs = self._pending.get(key)
+        if refs is None:
+            if len(self._pending) >= 64:     # forget sources whose chains are all gone or resolved
+                for k in [k for k, v in self._pending.items() if not any(r() is not None and r()._value is None for r in v)]:
+                    del self._pending[k]
+            refs = self._pending[key] = []
+        elif len(refs) >= 16:                # drop references to chains that are gone
+            refs[:] = [r for r in refs if r() is not None and r()._value is None]
+        refs.append(weakref.ref(lazy))
+
+    def _waiting(self, source):
+        """Recorded, unresolved, still referenced chains over `source`."""
+        out = []
+        for r in self._pending.get(id(source), ()):
+            l = r()
+            if l is not None and l._value is None and l._source is source:
+                out.append(l)
+        return out
+
+    def _siblings(self, lazy):
+        """The chains one kernel resolves together with `lazy` (first in the list): other chains over
+        the same source that nothing has continued yet (a chain that was continued is a shared
+        prefix, not an output), at most NFAD_MAX_OUTPUTS distinct programs in all."""
+        group, seen = [lazy], {tuple(lazy._program)}
+        for l in self._waiting(lazy._source):
+            if len(group) == 4:
+                break
+            if l is lazy or l._extended or (l._nops == 1 and l._native is not None) or tuple(l._program) in seen \
+                    or l._source_version != lazy._source_version or l.shape != lazy.shape:
+                continue
+            seen.add(tuple(l._program))
+            group.append(l)
+        return group
+
+    def _resolve_chains_over(self, tensor):
+        """Before `tensor` is written in place: every chain recorded over it takes its value now."""
+        for l in self._waiting(tensor):
+            l.materialize()
+        self._pending.pop(id(tensor), None)
 
     # ---- operand analysis
     def _operand(self, a, source):
@@ -290,7 +391,73 @@ class fuse(TorchFunctionMode):
             return None
         nops = 1 + sum(a._nops for a in lazies)
         native = (func, args, dict(kwargs)) if not lazies and op not in _FUSED_FUNCTIONALS else None
+        for a in lazies:
+            a._extended = True
         return Lazy(source, prog, self, nops, native)
+
+    # ---- the common cases without the general machinery: a primitive applied to a chain or a
+    # plain tensor, no keyword arguments.  Classification of the operator is cached per function
+    # object.  Returns a Lazy (NY or YY, logged), or _MISS for everything else.
+    def _fast(self, func, args):
+        info = _FUNC_KIND.get(func)
+        if info is None:
+            info = _FUNC_KIND[func] = _kind_of(func)
+        kind, tok, swap = info[0], info[1], info[2]
+        if kind == 1:
+            if len(args) != 1:
+                return _MISS
+            a = args[0]
+            ta = type(a)
+            if ta is Lazy:
+                if a._value is not None:
+                    return _MISS
+                a._extended = True
+                self.states.append("YY")
+                return Lazy(a._source, a._program + [tok], self, a._nops + 1, None)
+            if (ta is torch.Tensor or ta is torch.nn.Parameter) and self._eligible(a):
+                self.states.append("NY")
+                return Lazy(a, ["x", tok], self, 1, (func, args, {}))
+            return _MISS
+        if kind == 2:
+            if len(args) != 2:
+                return _MISS
+            l, r = (args[1], args[0]) if swap else args
+            source, lazy_in, progs = None, False, []
+            for o in (l, r):
+                to = type(o)
+                if to is Lazy:
+                    if o._value is not None or (source is not None and o._source is not source):
+                        return _MISS
+                    source, lazy_in = o._source, True
+                    progs.append(o._program)
+                elif to is torch.Tensor or to is torch.nn.Parameter:
+                    if source is not None and o is not source:
+                        return _MISS
+                    source = o
+                    progs.append(_X)
+                elif (to is float or to is int) and o == o and o not in (math.inf, -math.inf):
+                    progs.append([repr(float(o))])
+                else:
+                    return _MISS
+            if source is None:
+                return _MISS
+            # a plain tensor named before the chain it is the source of: re-check identity
+            for o in (l, r):
+                if type(o) is not Lazy and isinstance(o, torch.Tensor) and (o is not source or o.shape != source.shape):
+                    return _MISS
+            if not lazy_in and not self._eligible(source):
+                return _MISS
+            prog = progs[0] + progs[1] + [tok]
+            if len(prog) > 250:
+                return _MISS
+            nops = 1
+            for o in (l, r):
+                if type(o) is Lazy:
+                    o._extended = True
+                    nops += o._nops
+            self.states.append("YY" if lazy_in else "NY")
+            return Lazy(source, prog, self, nops, None if lazy_in else (func, args, {}))
+        return _MISS
 
     # ---- the state machine
     def _dispatch(self, func, args, kwargs):
@@ -301,10 +468,20 @@ class fuse(TorchFunctionMode):
             return self._step(func, args, kwargs)
 
     def _step(self, func, args, kwargs):
+        # a chain that has been resolved is an ordinary tensor from here on (its value may since have
+        # been written in place: the recorded program no longer describes it)
+        if any(isinstance(a, Lazy) and a._value is not None for a in _flatten(args) + _flatten(tuple(kwargs.values()))):
+            swap = lambda a: a._value if isinstance(a, Lazy) and a._value is not None else a
+            args = _map(args, swap)
+            kwargs = {k: _map((v,), swap)[0] for k, v in kwargs.items()}
+        written = _written_tensors(func, args, kwargs)
+        if written:
+            for t in written:
+                self._resolve_chains_over(t.materialize() if isinstance(t, Lazy) else t)
         flat = _flatten(args) + _flatten(tuple(kwargs.values()))
         input_is_fad = any(isinstance(a, Lazy) for a in flat)
         has_tensor = any(isinstance(a, torch.Tensor) for a in flat)
-        lazy = self._try_fad(func, args, kwargs) if has_tensor else None
+        lazy = self._try_fad(func, args, kwargs) if has_tensor and not written else None
         if has_tensor:
             self.states.append(classify(input_is_fad, lazy is not None))
         if lazy is not None:                       # NY or YY: record, execute nothing
@@ -316,19 +493,64 @@ class fuse(TorchFunctionMode):
         return func(*args, **kwargs)               # NN (or the operator after YN)
 
     def __torch_function__(self, func, types, args=(), kwargs=None):
+        # Fast paths for the bulk of a model's operators.  What kind of operator `func` is, is looked
+        # up once per function object.  (A lazy tensor nested deeper in the arguments than these
+        # checks look is still caught: the call then reaches Lazy.__torch_function__.)
+        info = _FUNC_KIND.get(func)
+        if info is None:
+            info = _FUNC_KIND[func] = _kind_of(func)
+        if info[0]:                                   # a plain primitive: NY / YY without the general machinery
+            if not kwargs:
+                r = self._fast(func, args)
+                if r is not _MISS:
+                    return r
+        elif not info[3]:                             # not a fad operator at all: ordinary execution (NN, not logged)
+            for a in args:
+                if type(a) is Lazy:
+                    break
+            else:
+                if kwargs:
+                    for v in kwargs.values():
+                        if type(v) is Lazy:
+                            break
+                    else:
+                        if not (self._pending and (info[4] or "out" in kwargs)):
+                            return func(*args, **kwargs)
+                elif not (self._pending and info[4]):
+                    return func(*args)
         kwargs = kwargs or {}
-        # Fast path for the bulk of a model's operators: not a fad operator and no lazy operand in
-        # sight -> ordinary execution (NN), not logged.  A lazy tensor nested deeper in the arguments
-        # is still caught: the call below then reaches Lazy.__torch_function__.
-        if getattr(func, "__name__", "") not in _OP_TABLE and not any(type(a) is Lazy for a in args) \
-                and not any(type(v) is Lazy for v in kwargs.values()):
-            return func(*args, **kwargs)
+        if info[3] and len(args) == 2 and not kwargs and type(args[0]) is torch.Tensor and type(args[1]) is torch.Tensor \
+                and args[0] is not args[1]:
+            return func(*args)                        # two different tensors: never a fad pair (Sec. III-A)
         return self._dispatch(func, args, kwargs)
 
 
 # attribute reads and bookkeeping calls that are not operators of the graph
 _PASSIVE = {"__get__", "__set__", "size", "dim", "stride", "is_contiguous", "numel", "__len__", "__repr__",
             "is_floating_point", "type", "data_ptr", "requires_grad_", "_make_wrapper_subclass", "detach"}
+
+
+_INPLACE_DUNDERS = {"__iadd__", "__isub__", "__imul__", "__itruediv__", "__idiv__", "__ifloordiv__", "__imod__",
+                    "__ipow__", "__iand__", "__ior__", "__ixor__", "__ilshift__", "__irshift__", "__setitem__"}
+
+
+def _may_write(name, kwargs) -> bool:
+    return (name.endswith("_") and not name.endswith("__")) or name in _INPLACE_DUNDERS or "out" in kwargs
+
+
+def _written_tensors(func, args, kwargs):
+    """Tensors an operator writes in place: `self` of a method whose name ends in an underscore (add_,
+    copy_, zero_, ...) or of an augmented assignment, and the out= arguments."""
+    name = getattr(func, "__name__", "")
+    if not _may_write(name, kwargs):
+        return []
+    out = []
+    if name != "" and (name.endswith("_") or name in _INPLACE_DUNDERS) and args and isinstance(args[0], torch.Tensor):
+        out.append(args[0])
+    o = kwargs.get("out")
+    if o is not None:
+        out += [t for t in _flatten((o,)) if isinstance(t, torch.Tensor)]
+    return out
 
 
 def _map(xs, f):

@@ -85,6 +85,64 @@ def test_two_consumers_of_one_source_give_two_outputs():
             extra_tol=chain_allowance(x64, d1) + chain_allowance(x64, d2))
 
 
+def test_two_outputs_recorded_before_the_first_use_are_one_kernel_with_two_saved_tangents():
+    """R^1 -> R^M inside the detector (Sec. IV-A, IV-B): both chains are recorded before anything
+    consumes them, so ONE forward kernel reads x once and writes both values and both tangents,
+    and ONE backward kernel merges the two upstream gradients at the source."""
+    n = 20_000
+    x = _x(n, 9350).to(DEV).requires_grad_(True)
+    x64 = inputs.storage_to_f64(x.detach().cpu())
+    w1 = inputs.to_storage(inputs.gaussian(n, 1.0, 9351), "f32")
+    w2 = inputs.to_storage(inputs.gaussian(n, 1.0, 9352), "f32")
+    with trace.fuse() as t:
+        h = torch.tanh(x)             # shared prefix: continued twice, never an output itself
+        a = h * x                     # output 1: x tanh x *
+        b = torch.sigmoid(h)          # output 2: x tanh sigmoid
+        assert t.kernels == []
+        la = (a * w1.to(DEV)).sum()   # first non-fad use (a different source): both chains resolve here
+        assert t.kernels == ["x tanh x * ; x tanh sigmoid"]
+        lb = (b * w2.to(DEV)).sum()
+        assert len(t.kernels) == 1
+    node = a.materialize().grad_fn
+    assert node is b.materialize().grad_fn and len(node.saved_tensors) == 2       # one node, M = 2 tangents
+    (la + lb).backward()
+    (y1, d1), (y2, d2) = ochain.eval_chain("x tanh x *", x64), ochain.eval_chain("x tanh sigmoid", x64)
+    compare(a.materialize().detach(), y1, torch.float32, "fused output 1", extra_tol=chain_allowance(x64, y1))
+    compare(b.materialize().detach(), y2, torch.float32, "fused output 2", extra_tol=chain_allowance(x64, y2))
+    g1, g2 = inputs.storage_to_f64(w1), inputs.storage_to_f64(w2)
+    g_ref = g1 * d1 + g2 * d2
+    compare(x.grad, g_ref, torch.float32, "merged gradient",
+            extra_tol=two_stage_budget(g1, d1, g_ref, torch.float32, chain_allowance(x64, d1))
+            + two_stage_budget(g2, d2, g_ref, torch.float32, chain_allowance(x64, d2)))
+
+
+def test_in_place_writes_keep_eager_semantics_on_the_gpu():
+    """The two ways an in-place operator could meet a deferred chain (see the host tests), end to end."""
+    x = _x(10_000, 9360).to(DEV)
+    x0 = x.clone()
+    x64 = inputs.storage_to_f64(x0.cpu())
+    with trace.fuse() as t:
+        y = F.silu(x)
+        y.mul_(2)                                  # y resolves, then is written in place
+        z = torch.tanh(y) * y                      # a new chain over the written tensor
+        u = torch.tanh(x) * x                      # a chain over x ...
+        x.add_(1)                                  # ... takes its value before x changes
+        out_z, out_u = z + 0 * x0, u + 0 * x0
+    s_ref = ochain.eval_chain("x x sigmoid *", x64)[0]
+    y_ref = 2 * s_ref
+    z_ref, dz_dy = ochain.eval_chain("x tanh x *", y_ref)
+    u_ref = ochain.eval_chain("x tanh x *", x64)[0]
+    # two stages: y carries its own bar and allowance (doubled by the in-place scaling), which the
+    # second chain's derivative scales; then the second chain's own allowance
+    from parity import tolerance
+    tol_y = 2 * (tolerance(torch.from_numpy(s_ref), torch.float32).numpy() + chain_allowance(x64, s_ref))
+    compare(out_z, z_ref, torch.float32, "chain over a written tensor",
+            extra_tol=np.abs(dz_dy) * tol_y + chain_allowance(y_ref, z_ref))
+    compare(out_u, u_ref, torch.float32, "chain resolved before its source was written",
+            extra_tol=chain_allowance(x64, u_ref))
+    assert torch.equal(x, x0 + 1)
+
+
 def test_mixing_sources_ends_both_chains():
     x = _x(5_000, 9400).to(DEV)
     w = _x(5_000, 9401).to(DEV)

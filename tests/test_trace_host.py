@@ -171,3 +171,82 @@ def test_recorded_program_of_a_functional_means_what_the_framework_computes(name
     # 1e-7: the framework's own fp64 kernels carry a few fp32 constants (1/6, the softplus threshold)
     assert np.allclose(y, y64.detach().numpy(), rtol=1e-7, atol=1e-7), (name, program)
     assert np.allclose(d, d64.numpy(), rtol=1e-7, atol=1e-7), (name, program)
+
+
+# ------------------------------------------------------------------ eager semantics under mutation
+@pytest.fixture
+def interpreted_chains(monkeypatch):
+    """Chains resolve through the fp64 interpreter instead of the GPU library (host tests of the
+    detector's bookkeeping only: which program runs on which values)."""
+    from paper_2209_10778_amd import autograd as A
+
+    def one(x, prog):
+        v, _ = ochain.eval_chain(prog, x.detach().double().numpy())
+        return torch.from_numpy(v).to(x.dtype).view(x.shape)
+
+    monkeypatch.setattr(A, "chain", one)
+    monkeypatch.setattr(A, "chain_multi", lambda x, progs: tuple(one(x, p) for p in progs))
+
+
+def test_in_place_operator_on_a_resolved_chain_leaves_no_stale_program(interpreted_chains):
+    x = torch.tensor([0.5, -0.7, 2.0, -3.0])
+    with trace.fuse(require_cuda=False) as t:
+        y = F.silu(x)
+        y.mul_(2)                         # resolves y (YN) and writes the value in place
+        z = torch.tanh(y)                 # must see 2 * silu(x): y is an ordinary tensor now
+        out = z + torch.zeros(4)          # a non-fad use
+    assert t.kernels == ["x x sigmoid *"]
+    assert torch.allclose(out, torch.tanh(2 * F.silu(x)), atol=1e-6)
+
+
+def test_in_place_operator_on_a_source_resolves_the_chains_recorded_over_it(interpreted_chains):
+    x = torch.tensor([0.5, -0.7, 2.0, -3.0])
+    x0 = x.clone()
+    with trace.fuse(require_cuda=False) as t:
+        y = torch.tanh(x) * x
+        assert isinstance(y, trace.Lazy) and t.kernels == []
+        x.add_(1)                         # the chain takes its value BEFORE the write
+        assert t.kernels == ["x tanh x *"]
+        out = y + torch.zeros(4)
+    assert torch.allclose(out, torch.tanh(x0) * x0, atol=1e-6) and torch.equal(x, x0 + 1)
+    # also through an augmented assignment and an out= argument
+    for write in (lambda v: v.__iadd__(1.0), lambda v: torch.add(v, 1.0, out=v), lambda v: v.copy_(torch.ones(4))):
+        x = x0.clone()
+        with trace.fuse(require_cuda=False) as t:
+            y = torch.exp(-x) * x
+            write(x)
+            out = y + torch.zeros(4)
+        assert torch.allclose(out, torch.exp(-x0) * x0, atol=1e-6)
+
+
+def test_source_modified_behind_the_detectors_back_is_an_error(interpreted_chains):
+    x = torch.tensor([0.5, -0.7, 2.0])
+    with trace.fuse(require_cuda=False):
+        y = torch.tanh(x) * x
+    x.add_(1)                             # outside the context: nothing can intercept this
+    with pytest.raises(RuntimeError, match="modified in place"):
+        y.sum()
+    base = torch.tensor([0.5, -0.7, 2.0])
+    with trace.fuse(require_cuda=False):
+        y = torch.tanh(base) * base
+        base.view(-1)[0:1].zero_()        # through a view: caught by the version counter
+        with pytest.raises(RuntimeError, match="modified in place"):
+            y.sum()
+
+
+def test_chains_over_one_source_waiting_to_be_consumed_are_resolved_together(interpreted_chains):
+    """R^1 -> R^M: two outputs recorded before the first non-fad use form ONE group; the shared
+    prefix h is not an output; a chain recorded after the group was resolved gets its own kernel."""
+    x = torch.tensor([0.5, -0.7, 2.0, -3.0])
+    with trace.fuse(require_cuda=False) as t:
+        h = torch.tanh(x)                 # continued by both chains below: a prefix, not an output
+        a = h * x
+        b = torch.sigmoid(h)
+        sa = a.sum()                      # first non-fad use: a and b are resolved by one kernel
+        assert t.kernels == ["x tanh x * ; x tanh sigmoid"] and b._value is not None and h._value is None
+        sb = b.sum()                      # already resolved: no further kernel
+        c = torch.exp(-x) * x
+        sc = c.sum()
+    assert t.kernels == ["x tanh x * ; x tanh sigmoid", "x neg exp x *"]
+    assert torch.allclose(sa, (torch.tanh(x) * x).sum()) and torch.allclose(sb, torch.sigmoid(torch.tanh(x)).sum())
+    assert torch.allclose(sc, (torch.exp(-x) * x).sum())
