@@ -15,6 +15,7 @@ namespace nfad {
 template <int KIND>
 struct FwdOp {
   static constexpr int kIn = 1, kOut = 2;
+  static constexpr bool kLight = KIND == kSwish;   // one exponential, one reciprocal and four more operations
   template <bool kWide>
   __device__ __forceinline__ static void apply(const float (&in)[kIn], float (&out)[kOut]) {
     Act<KIND>::template eval<kWide>(in[0], out[0], out[1]);
@@ -70,6 +71,7 @@ struct SaveAllBwdOp;
 template <>
 struct SaveAllFwdOp<kSwish> {  // v1 = sigmoid(x), v2 = x, v3 = v1 v2; saves v1
   static constexpr int kIn = 1, kOut = 2;
+  static constexpr bool kLight = true;
   template <bool kWide>
   __device__ __forceinline__ static void apply(const float (&in)[kIn], float (&out)[kOut]) {
     const float v1 = sigmoid_f(in[0]);

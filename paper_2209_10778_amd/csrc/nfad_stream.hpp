@@ -76,21 +76,21 @@ static Geometry shape_geometry(size_t n, int elems_per_vec, int waves_per_cu, bo
   return {(unsigned)grid, (unsigned)Sh::kThreads, lds_reservation(waves_per_cu, Sh::kThreads, device_info().lds_per_cu),
           small};
 }
-template <int NIN, int NOUT, typename T>
+template <int NIN, int NOUT, typename T, bool LIGHT>
 static Geometry rule_geometry(size_t n) {
-  using R = ShapeRule<NIN, NOUT, T>;
+  using R = ShapeRule<NIN, NOUT, T, LIGHT>;
   constexpr int kVec = 16 / (int)sizeof(T);
   if (R::kTwoShapes && (unsigned long long)n * sizeof(T) * (NIN + NOUT) < R::kSmallBytes)
     return shape_geometry<typename R::Small>(n, kVec, R::kSmallWavesPerCu, true);
   return shape_geometry<typename R::Large>(n, kVec, R::kLargeWavesPerCu, false);
 }
 // Geometry of the vector kernel of an operation with NIN inputs and NOUT outputs on `dtype` storage.
-template <int NIN, int NOUT>
+template <int NIN, int NOUT, bool LIGHT>
 static Geometry default_geometry(int dtype, size_t n) {
   switch (dtype) {
-    case NFAD_F32: return rule_geometry<NIN, NOUT, float>(n);
-    case NFAD_F16: return rule_geometry<NIN, NOUT, _Float16>(n);
-    default: return rule_geometry<NIN, NOUT, __bf16>(n);
+    case NFAD_F32: return rule_geometry<NIN, NOUT, float, LIGHT>(n);
+    case NFAD_F16: return rule_geometry<NIN, NOUT, _Float16, LIGHT>(n);
+    default: return rule_geometry<NIN, NOUT, __bf16, LIGHT>(n);
   }
 }
 static Geometry scalar_geometry(size_t n) {
@@ -128,7 +128,7 @@ static Ptrs<NIN, NOUT> advanced(const Ptrs<NIN, NOUT>& p, size_t bytes) {
 }
 // Runs a call according to its plan.  launch_vec(ptrs, n, geometry) and launch_scalar(ptrs, n,
 // geometry) enqueue the two kernels and return a hipError_t.
-template <int NIN, int NOUT, class LaunchVec, class LaunchScalar>
+template <int NIN, int NOUT, bool LIGHT = false, class LaunchVec, class LaunchScalar>
 static int launch_planned(const Ptrs<NIN, NOUT>& p, size_t n, int dtype, LaunchVec launch_vec,
                           LaunchScalar launch_scalar) {
   const size_t elem_bytes = dtype == NFAD_F32 ? 4 : 2;
@@ -140,7 +140,7 @@ static int launch_planned(const Ptrs<NIN, NOUT>& p, size_t n, int dtype, LaunchV
     if (plan.head) e = launch_scalar(p, plan.head, scalar_geometry(plan.head));
     if (e == hipSuccess) {
       const size_t rest = n - plan.head;
-      e = launch_vec(advanced(p, plan.head * elem_bytes), rest, default_geometry<NIN, NOUT>(dtype, rest));
+      e = launch_vec(advanced(p, plan.head * elem_bytes), rest, default_geometry<NIN, NOUT, LIGHT>(dtype, rest));
     }
   }
   return e == hipSuccess ? NFAD_OK : NFAD_ELAUNCH;
@@ -150,11 +150,11 @@ template <class Op, typename T, int DTYPE>
 static int launch(const void* const (&in)[Op::kIn], void* const (&out)[Op::kOut], size_t n,
                   hipStream_t stream, const typename OpParams<Op>::type& prm) {
   using P = Ptrs<Op::kIn, Op::kOut>;
-  using R = ShapeRule<Op::kIn, Op::kOut, T>;
+  using R = ShapeRule<Op::kIn, Op::kOut, T, OpLight<Op>::value>;
   P p;
   for (int i = 0; i < Op::kIn; ++i) p.in[i] = in[i];
   for (int o = 0; o < Op::kOut; ++o) p.out[o] = out[o];
-  return launch_planned(
+  return launch_planned<Op::kIn, Op::kOut, OpLight<Op>::value>(
       p, n, DTYPE,
       [stream, &prm](const P& q, size_t m, Geometry g) {
         if (R::kTwoShapes && g.small)

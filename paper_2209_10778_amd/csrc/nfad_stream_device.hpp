@@ -38,7 +38,8 @@ struct Shape {
 //    with no cap on resident waves: best or within 1-2 % of best at every size.
 //  * Kernels that read one tensor and write several (the forward pass of the method) run it
 //    capped at 20 waves per compute unit for fp32 storage and 24 for 16-bit storage (twice the
-//    arithmetic per byte keeps a wave alive longer).  A launch that moves less than 96 MB is
+//    arithmetic per byte keeps a wave alive longer; an operation that declares kLight, the
+//    cheapest arithmetic, keeps 20 for 16-bit storage too).  A launch that moves less than 96 MB is
 //    over before a steady state forms, and then what counts is how fast the grid is handed
 //    out: four times fewer, fatter blocks (two waves, two accesses per lane) and no cap.
 template <bool C, class A, class B>
@@ -49,12 +50,12 @@ template <class A, class B>
 struct SelectType<false, A, B> {
   using type = B;
 };
-template <int NIN, int NOUT, typename T>
+template <int NIN, int NOUT, typename T, bool LIGHT = false>
 struct ShapeRule {
   static constexpr bool kFanOut = NIN == 1 && NOUT >= 2;
   using Large = Shape<64, 1, true>;
   using Small = typename SelectType<kFanOut, Shape<128, 2, true>, Large>::type;
-  static constexpr int kLargeWavesPerCu = kFanOut ? (sizeof(T) == 4 ? 20 : 24) : 0;   // 0 = no cap
+  static constexpr int kLargeWavesPerCu = kFanOut ? ((sizeof(T) == 4 || LIGHT) ? 20 : 24) : 0;   // 0 = no cap
   static constexpr int kSmallWavesPerCu = 0;
   static constexpr bool kTwoShapes = kFanOut;
   static constexpr unsigned long long kSmallBytes = 96ull << 20;   // bytes moved per launch
@@ -121,6 +122,16 @@ struct NoParams {};
 template <class...>
 struct VoidType {
   using type = void;
+};
+// An operation whose arithmetic is so light that its waves live hardly longer than their memory
+// accesses declares `static constexpr bool kLight = true` (see ShapeRule).
+template <class Op, class = void>
+struct OpLight {
+  static constexpr bool value = false;
+};
+template <class Op>
+struct OpLight<Op, typename VoidType<decltype(Op::kLight)>::type> {
+  static constexpr bool value = Op::kLight;
 };
 template <class Op, class = void>
 struct OpParams {

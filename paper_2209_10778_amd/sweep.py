@@ -17,6 +17,10 @@ and load/store helpers with the launch shape as run-time arguments); `--lib` add
 own entry points (their built-in shape selection) as rows.  Results go to stdout as a
 markdown table sorted by time and, with --out, to a JSON-lines file.
 
+`--phased` runs the other experiment the library carries: reads and writes separated in time
+across the whole chip by the constant-rate clock (nfad_sweep_launch_phased), against the same
+kernels unphased and libnfad's own.
+
 This is a measurement tool: nothing in libnfad or its binding depends on it.
 """
 from __future__ import annotations
@@ -67,6 +71,8 @@ def sweep_lib() -> ctypes.CDLL:
         L.nfad_sweep_launch.argtypes = [ci, ci, ci, ci, ci, ci, ci, ci, ctypes.c_longlong, ci, vpp, vpp,
                                         ctypes.c_size_t, vp]
         L.nfad_sweep_launch.restype = ci
+        L.nfad_sweep_launch_phased.argtypes = [ci, ci, ci, ci, ci, ci, ci, ci, vpp, vpp, ctypes.c_size_t, vp]
+        L.nfad_sweep_launch_phased.restype = ci
         _sweep_lib = L
     return _sweep_lib
 
@@ -82,6 +88,20 @@ def launch(pattern: str, dtype: str, shape: dict, ins, outs, n: int, stream=None
                                        a_in, a_out, n, st)
     if rc != 0:
         raise B.NfadError(rc, f"nfad_sweep_launch({pattern}, {shape})")
+
+
+def launch_phased(pattern: str, dtype: str, unroll: int, waves: int, persistent: bool, period_ticks: int,
+                  read_ticks: int, ins, outs, n: int, stream=None) -> None:
+    """One launch of an arithmetic pattern with its loads and stores confined to alternating phases of
+    the chip-wide 100 MHz clock (period_ticks = 0: no phasing).  One-wave blocks, `waves` of them
+    resident per compute unit, `unroll` 16-byte vectors per lane and tensor per period."""
+    a_in = (ctypes.c_void_p * len(ins))(*[t.data_ptr() for t in ins])
+    a_out = (ctypes.c_void_p * len(outs))(*[t.data_ptr() for t in outs])
+    st = torch.cuda.current_stream().cuda_stream if stream is None else stream
+    rc = sweep_lib().nfad_sweep_launch_phased(PATTERNS[pattern][0], _DT[dtype], unroll, 1, waves, int(persistent),
+                                              period_ticks, read_ticks, a_in, a_out, n, st)
+    if rc != 0:
+        raise B.NfadError(rc, f"nfad_sweep_launch_phased({pattern})")
 
 
 def _ints(s: str):
@@ -109,6 +129,12 @@ def parse_args(argv=None):
     ap.add_argument("--top", type=int, default=0, help="print only the best N rows per (size, pattern)")
     ap.add_argument("--out", default=None, help="append one JSON line per row to this file")
     ap.add_argument("--no-verify", action="store_true")
+    ap.add_argument("--phased", action="store_true",
+                    help="the read/write phasing experiment on the arithmetic patterns given (fwd_*, bwd): --waves = "
+                         "resident one-wave blocks per compute unit, --unroll = vectors per lane per period (2,4,8,16), "
+                         "--grid 0 = one block per tile / c1 = persistent; phases sized for --phase-scale x "
+                         "(7.1 TB/s reads, 6.9 TB/s writes)")
+    ap.add_argument("--phase-scale", default="0.9,1.0,1.1")
     return ap.parse_args(argv)
 
 
@@ -171,9 +197,25 @@ def main(argv=None):
             moved = (n_in + n_out) * nbytes
             use_graph = moved < 64e6
             rows = []
-            for th, u, adj, ntl, nts, wv, gr, ch in itertools.product(
+            if args.phased:
+                assert arith and pattern in ("bwd",) + tuple(k for k in PATTERNS if k.startswith("fwd_")) and dtype != "f16"
+                for wv, u, gr in itertools.product(_ints(args.waves), _ints(args.unroll), args.grid.split(",")):
+                    persistent = gr != "0"
+                    variants = [("unphased", 0, 0)]
+                    chunk = cus * wv * u * 1024           # bytes per tensor per period, chip-wide
+                    for sc in [float(v) for v in args.phase_scale.split(",")]:
+                        read = int(n_in * chunk / (7.1e12 * sc) * 1e8)
+                        variants.append((f"phased x{sc}: period {10 * (read + int(n_out * chunk / (6.9e12 * sc) * 1e8))} ns, "
+                                         f"reads in the first {10 * read} ns", read + int(n_out * chunk / (6.9e12 * sc) * 1e8), read))
+                    for label, period, read in variants:
+                        def fn(s, st, wv=wv, u=u, persistent=persistent, period=period, read=read):
+                            launch_phased(pattern, dtype, u, wv, persistent, period, read, s["in"][:n_in],
+                                          s["out"][:n_out], n, st)
+                        rows.append({"size": size, "pattern": pattern, "fn": fn, "shape": {"waves": wv, "unroll": u, "persistent": persistent, "period": period, "read": read},
+                                     "label": f"T64 U{u} w{wv} {'persistent' if persistent else 'one block per tile'} {label}"})
+            for th, u, adj, ntl, nts, wv, gr, ch in ([] if args.phased else itertools.product(
                     _ints(args.threads), _ints(args.unroll), _ints(args.adjacent), _ints(args.ntl),
-                    _ints(args.nts), _ints(args.waves), args.grid.split(","), _ints(args.chunk)):
+                    _ints(args.nts), _ints(args.waves), args.grid.split(","), _ints(args.chunk))):
                 if arith and (nts == 0 or adj or ch or u > 4 or th > 512):
                     continue    # the arithmetic patterns are libnfad's own kernel template: fewer knobs
                 shape = {"threads": th, "unroll": u, "adjacent": adj, "ntl": ntl, "nts": nts, "waves": wv,

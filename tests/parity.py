@@ -11,7 +11,8 @@ Two derived budgets exist, for results the bar was not written for:
   * a gradient computed from a tangent that was itself rounded to storage by the GPU (forward
     feeding backward): the tangent may be off by its own bar, which the upstream gradient
     scales, and the product is rounded once more: |gy| * bar_T(dydx) + bar_T(gx)
-    (`two_stage_budget`);
+    (`two_stage_budget`; `saveall_two_stage_budget` is the same for the save-all baseline, whose
+    backward pass consumes several GPU-stored tensors);
   * a composed chain of up to a dozen fp32 primitives: each primitive rounds (2^-24 relative)
     and the hardware exponential's argument rounding grows with |x|, so on top of the bar
     5e-7 * max(1, |x|) * max(1, |ref|) (`chain_allowance`; eight roundings of a value of
@@ -52,6 +53,29 @@ def two_stage_budget(gy64, d_ref64, gx_ref64, dtype: torch.dtype, d_allowance=No
     if d_allowance is not None:
         tol_d = tol_d + np.asarray(d_allowance)
     return np.abs(np.asarray(gy64)) * tol_d
+
+
+def saveall_two_stage_budget(kind, gy64, x64, dtype: torch.dtype):
+    """The same budget for the save-all baseline when its backward pass consumes the intermediates
+    that the GPU forward pass stored: each stored tensor may be off by its own bar, and the
+    backward formula passes that on with the sensitivity d gx / d saved_j, taken here from the
+    oracle by displacing one stored tensor at a time by its bar (both signs, the larger effect);
+    numpy float64, to be passed as `extra_tol`."""
+    import oracle
+    x64 = np.asarray(x64, dtype=np.float64)
+    one = np.ones_like(x64)
+    _, saved = oracle.saveall_fwd(kind, x64)
+    base = oracle.saveall_bwd(kind, one, saved)
+    budget = np.zeros_like(x64)
+    for j in range(1, len(saved)):
+        bar_j = tolerance(torch.as_tensor(saved[j], dtype=torch.float64), dtype).numpy()
+        effect = np.zeros_like(x64)
+        for sign in (1.0, -1.0):
+            moved = list(saved)
+            moved[j] = saved[j] + sign * bar_j
+            effect = np.maximum(effect, np.abs(oracle.saveall_bwd(kind, one, moved) - base))
+        budget += effect
+    return np.abs(np.asarray(gy64)) * budget
 
 
 def compare(got: torch.Tensor, ref64, dtype: torch.dtype, what: str = "", flat_abs: float | None = None,

@@ -8,7 +8,7 @@ from oracle import chain as ochain
 import paper_2209_10778_amd as nfad
 from paper_2209_10778_amd import autograd as A
 from paper_2209_10778_amd import inputs
-from parity import chain_allowance, compare, two_stage_budget
+from parity import chain_allowance, compare, saveall_two_stage_budget, two_stage_budget
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -30,9 +30,11 @@ def test_value_and_gradient(name, mode):
     y.backward(gy.to(DEV).view(shape))
     compare(y.detach(), y_ref, torch.float32, f"{name} {mode} y")
     g_ref = gy64 * d_ref
-    # fad: the GPU's own stored tangent feeds the product (two-stage budget); the two baselines
-    # compute gy * f'(x) in one kernel (the stated bar, no allowance)
-    extra = two_stage_budget(gy64, d_ref, g_ref, torch.float32) if mode == "fad" else None
+    # fad and save-all: the backward pass consumes what the GPU forward pass stored (two-stage
+    # budgets); recomputation derives gy * f'(x) in one kernel (the stated bar, no allowance)
+    extra = {"fad": lambda: two_stage_budget(gy64, d_ref, g_ref, torch.float32),
+             "saveall": lambda: saveall_two_stage_budget(KIND[name], gy64, x64, torch.float32),
+             "recompute": lambda: None}[mode]()
     st = compare(xd.grad, g_ref, torch.float32, f"{name} {mode} grad", extra_tol=extra)
     print(f"\n[autograd {name} {mode}] grad err / stated bar {st['max_over_bar']:.3f}")
 
