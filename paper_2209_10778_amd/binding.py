@@ -74,8 +74,8 @@ def lib() -> ctypes.CDLL:
 
 
 def _stream(stream) -> int:
-    if stream is None:
-        return torch.cuda.current_stream().cuda_stream
+    if stream is None:                       # the current device's current stream, without a Stream object
+        return torch._C._cuda_getCurrentRawStream(torch._C._cuda_getDevice())
     if isinstance(stream, torch.cuda.Stream):
         return stream.cuda_stream
     return int(stream)

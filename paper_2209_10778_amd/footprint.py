@@ -17,7 +17,8 @@ budget: total peak memory is linear in the batch (weights + a per-sample cost), 
 measured at two batch sizes, extrapolated to the budget, and the extrapolated batch is then
 run once to confirm that it fits.
 
-Run:  python -m paper_2209_10778_amd.footprint [--dtype bf16] [--batch 32] [--budget-gib 16] [--whole-models bert|resnet|both]
+Run:  python -m paper_2209_10778_amd.footprint [--dtype bf16] [--batch 32] [--time-batch 128] [--budget-gib 16]
+                                                 [--whole-models bert|resnet|both]
 Prints one JSON line per (block, activation).
 """
 from __future__ import annotations
@@ -150,14 +151,17 @@ def measure(make_block, x, steps=5):
     del y
     block.zero_grad(set_to_none=True)
     x.grad = None
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        block(x).float().square().mean().backward()
-        block.zero_grad(set_to_none=True)
-        x.grad = None
-    torch.cuda.synchronize()
+    rounds = []
+    for _ in range(3 if steps else 0):                   # median of three rounds of `steps` steps
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            block(x).float().square().mean().backward()
+            block.zero_grad(set_to_none=True)
+            x.grad = None
+        torch.cuda.synchronize()
+        rounds.append((time.perf_counter() - t0) / steps * 1e3)
     del block
-    return held, peak, (time.perf_counter() - t0) / max(steps, 1) * 1e3, base + peak
+    return held, peak, sorted(rounds)[1] if rounds else 0.0, base + peak
 
 
 def _progress(msg):
@@ -190,6 +194,8 @@ def main():
     ap.add_argument("--batch", type=int, default=32)
     ap.add_argument("--whole-models", choices=("bert", "resnet", "both"), default=None,
                     help="BERT-base encoder (12 layers) and/or ResNet-50 instead of single blocks")
+    ap.add_argument("--time-batch", type=int, default=0,
+                    help="also time one step at this (larger) batch, where the GPU and not the interpreter sets the pace")
     ap.add_argument("--budget-gib", type=float, default=16.0,
                     help="memory budget of the maximum-batch-size figure (0 = skip it)")
     args = ap.parse_args()
@@ -220,6 +226,13 @@ def main():
                 _progress(f"{name} {kind} {regime}: batch {args.batch} measured, {ms:.2f} ms/step")
                 row["regimes"][regime] = {"held_after_fwd_MiB": round(held / 2 ** 20, 1),
                                           "peak_MiB": round(peak / 2 ** 20, 1), "ms_per_step": round(ms, 3)}
+            if args.time_batch:
+                xl = make_x(args.time_batch)
+                for regime in REGIMES:
+                    ms = measure(maker(kind, regime), xl)[2]
+                    _progress(f"{name} {kind} {regime}: batch {args.time_batch} timed, {ms:.2f} ms/step")
+                    row["regimes"][regime][f"ms_per_step_batch{args.time_batch}"] = round(ms, 3)
+                del xl
             r = row["regimes"]
             row["held_composite_over_fad"] = round(r["composite"]["held_after_fwd_MiB"] / r["fad"]["held_after_fwd_MiB"], 3)
             row["held_native_over_fad"] = round(r["native"]["held_after_fwd_MiB"] / r["fad"]["held_after_fwd_MiB"], 3)

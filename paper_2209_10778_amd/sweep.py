@@ -21,6 +21,10 @@ markdown table sorted by time and, with --out, to a JSON-lines file.
 across the whole chip by the constant-rate clock (nfad_sweep_launch_phased), against the same
 kernels unphased and libnfad's own.
 
+`--skew` places the tensors of a buffer set inside one allocation, 256 MiB-aligned starts plus
+k x SKEW bytes for the k-th tensor (one set of rows per value): whether the relative placement
+of the streams in memory matters.
+
 This is a measurement tool: nothing in libnfad or its binding depends on it.
 """
 from __future__ import annotations
@@ -39,6 +43,7 @@ from . import binding as B
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SWEEP_LIB = os.path.join(_HERE, "libnfad_sweep.so")
+_SKEW_ALIGN = 1 << 28
 
 # pattern name -> (code, tensors read, tensors written, has arithmetic)
 PATTERNS = {
@@ -126,6 +131,8 @@ def parse_args(argv=None):
     ap.add_argument("--launches", type=int, default=60)
     ap.add_argument("--warm-ms", type=float, default=25.0)
     ap.add_argument("--sets", type=int, default=0, help="rotating buffer sets (0 = enough for > 1 GiB)")
+    ap.add_argument("--skew", default="", help="byte offsets (multiples of 16) of successive tensors beyond "
+                                               "256 MiB-aligned starts; empty = separate allocations")
     ap.add_argument("--top", type=int, default=0, help="print only the best N rows per (size, pattern)")
     ap.add_argument("--out", default=None, help="append one JSON line per row to this file")
     ap.add_argument("--no-verify", action="store_true")
@@ -187,10 +194,25 @@ def main(argv=None):
         g = torch.Generator(device="cpu").manual_seed(1234)
         host = [torch.randn(n, generator=g, dtype=torch.float32).to(td) for _ in range(2)]
         host[1].mul_(0.1)
-        sets = []
-        for _ in range(nsets):
-            sets.append({"in": [h.to(dev) for h in host],
-                         "out": [torch.empty(n, dtype=td, device=dev) for _ in range(2)]})
+        placements = {}
+        if not args.skew:
+            placements[None] = [{"in": [h.to(dev) for h in host],
+                                 "out": [torch.empty(n, dtype=td, device=dev) for _ in range(2)]} for _ in range(nsets)]
+        else:
+            skews = _ints(args.skew)
+            assert all(k >= 0 and k % 16 == 0 for k in skews), "--skew: non-negative multiples of 16"
+            span = -(-nbytes // _SKEW_ALIGN) * _SKEW_ALIGN
+            arenas = [torch.empty(4 * span + 3 * max(skews) + _SKEW_ALIGN, dtype=torch.uint8, device=dev)
+                      for _ in range(nsets * len(skews))]
+            for j, skew in enumerate(skews):
+                placements[skew] = []
+                for arena in arenas[j * nsets:(j + 1) * nsets]:
+                    first = (-arena.data_ptr()) % _SKEW_ALIGN
+                    t = [arena[first + k * (span + skew):first + k * (span + skew) + nbytes].view(td) for k in range(4)]
+                    t[0].copy_(host[0])
+                    t[1].copy_(host[1])
+                    placements[skew].append({"in": t[:2], "out": t[2:]})
+        sets = next(iter(placements.values()))
         sink = torch.zeros(4, dtype=torch.int32, device=dev)
         for pattern in args.patterns.split(","):
             code, n_in, n_out, arith = PATTERNS[pattern]
@@ -213,9 +235,9 @@ def main(argv=None):
                                           s["out"][:n_out], n, st)
                         rows.append({"size": size, "pattern": pattern, "fn": fn, "shape": {"waves": wv, "unroll": u, "persistent": persistent, "period": period, "read": read},
                                      "label": f"T64 U{u} w{wv} {'persistent' if persistent else 'one block per tile'} {label}"})
-            for th, u, adj, ntl, nts, wv, gr, ch in ([] if args.phased else itertools.product(
+            for th, u, adj, ntl, nts, wv, gr, ch, skew in ([] if args.phased else itertools.product(
                     _ints(args.threads), _ints(args.unroll), _ints(args.adjacent), _ints(args.ntl),
-                    _ints(args.nts), _ints(args.waves), args.grid.split(","), _ints(args.chunk))):
+                    _ints(args.nts), _ints(args.waves), args.grid.split(","), _ints(args.chunk), list(placements))):
                 if arith and (nts == 0 or adj or ch or u > 4 or th > 512):
                     continue    # the arithmetic patterns are libnfad's own kernel template: fewer knobs
                 shape = {"threads": th, "unroll": u, "adjacent": adj, "ntl": ntl, "nts": nts, "waves": wv,
@@ -223,8 +245,10 @@ def main(argv=None):
 
                 def fn(s, st, shape=shape):
                     launch(pattern, dtype, shape, s["in"][:n_in], s["out"][:n_out] if n_out else [sink], n, st)
-                rows.append({"size": size, "pattern": pattern, "shape": shape, "fn": fn, "label":
-                             f"T{th} U{u}{' adj' if adj else ''} ntl{ntl} nts{nts} w{wv} g{gr} c{ch}"})
+                rows.append({"size": size, "pattern": pattern, "shape": shape, "fn": fn, "skew": skew,
+                             "sets": placements[skew], "label":
+                             f"T{th} U{u}{' adj' if adj else ''} ntl{ntl} nts{nts} w{wv} g{gr} c{ch}"
+                             + ("" if skew is None else f" skew {skew}")})
             if args.lib:
                 lib_fn = None
                 if pattern in ("r1w2",) or pattern.startswith("fwd_"):
@@ -239,21 +263,25 @@ def main(argv=None):
                     lib_fn = (lambda s, st, kind=kind: B.nfad_recompute_fwd(kind, s["in"][0], s["out"][0], st))
                     name = f"libnfad nfad_recompute_fwd({B.KIND_NAMES[kind]})"
                 if lib_fn is not None:
-                    rows.append({"size": size, "pattern": pattern, "shape": None, "fn": lib_fn, "label": name})
+                    for skew in placements:
+                        rows.append({"size": size, "pattern": pattern, "shape": None, "fn": lib_fn, "skew": skew,
+                                     "sets": placements[skew],
+                                     "label": name + ("" if skew is None else f" skew {skew}")})
 
             if not args.no_verify:
                 for r in rows:
                     if r["shape"] is not None:
-                        for o in sets[0]["out"]:
+                        first = r.get("sets", sets)[0]
+                        for o in first["out"]:
                             o.zero_()
-                        r["fn"](sets[0], stream.cuda_stream)
-                        _verify(pattern, dtype, sets[0]["in"][:n_in], sets[0]["out"][:n_out], n)
+                        r["fn"](first, stream.cuda_stream)
+                        _verify(pattern, dtype, first["in"][:n_in], first["out"][:n_out], n)
 
-            def runner(fn, count):
+            def runner(fn, count, own):
                 def enqueue():
                     st = torch.cuda.current_stream().cuda_stream
                     for i in range(count):
-                        fn(sets[i % nsets], st)
+                        fn(own[i % nsets], st)
                 if not use_graph:
                     return enqueue
                 gph = torch.cuda.CUDAGraph()
@@ -262,7 +290,7 @@ def main(argv=None):
                 return gph.replay
 
             for r in rows:
-                r["run"] = runner(r["fn"], args.launches)
+                r["run"] = runner(r["fn"], args.launches, r.pop("sets", sets))
                 r["us"] = []
             for rnd in range(args.rounds):
                 for r in rows:
@@ -297,7 +325,7 @@ def main(argv=None):
                       f"{' '.join(f'{v:.2f}' for v in r['us'])} |")
             sys.stdout.flush()
             results += rows
-        del sets
+        del sets, placements
         torch.cuda.empty_cache()
     if args.out:
         os.makedirs(os.path.dirname(os.path.abspath(args.out)), exist_ok=True)

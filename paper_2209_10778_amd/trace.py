@@ -204,8 +204,8 @@ def _op_name(func):
 
 _MISS = object()
 _X = ["x"]
-# function object -> (kind, token, operands swapped, is a fad operator of any sort, may write in place);
-# kind 1: plain unary primitive, 2: plain binary arithmetic, 0: neither
+# function object -> (kind, token, operands swapped, is a fad operator of any sort, may write in place,
+# is an attribute read); kind 1: plain unary primitive, 2: plain binary arithmetic, 3: power, 0: neither
 _FUNC_KIND = {}
 _PLAIN_UNARY = {"neg": "neg", "exp": "exp", "log": "log", "tanh": "tanh", "sigmoid": "sigmoid", "erf": "erf",
                 "relu": "relu", "abs": "abs", "sqrt": "sqrt"}
@@ -218,10 +218,12 @@ def _kind_of(func):
     op = _OP_TABLE.get(name)
     writes = (name.endswith("_") and not name.endswith("__")) or name in _INPLACE_DUNDERS
     if op in _PLAIN_UNARY:
-        return (1, _PLAIN_UNARY[op], False, True, writes)
+        return (1, _PLAIN_UNARY[op], False, True, writes, False)
     if op in _PLAIN_BINARY:
-        return (2,) + _PLAIN_BINARY[op] + (True, writes)
-    return (0, None, False, op is not None, writes)
+        return (2,) + _PLAIN_BINARY[op] + (True, writes, False)
+    if op == "pow":
+        return (3, None, False, True, writes, False)
+    return (0, None, False, op is not None, writes, name in _PASSIVE)
 
 
 class fuse(TorchFunctionMode):
@@ -457,6 +459,21 @@ class fuse(TorchFunctionMode):
                     nops += o._nops
             self.states.append("YY" if lazy_in else "NY")
             return Lazy(source, prog, self, nops, None if lazy_in else (func, args, {}))
+        if kind == 3:                                 # a small integer power: repeated multiplication
+            if len(args) != 2 or type(args[1]) is not int or not 2 <= args[1] <= 8:
+                return _MISS
+            a, k = args
+            ta = type(a)
+            if ta is Lazy:
+                if a._value is not None or len(a._program) * k + k > 250:
+                    return _MISS
+                a._extended = True
+                self.states.append("YY")
+                return Lazy(a._source, a._program + (a._program + ["*"]) * (k - 1), self, a._nops + 1, None)
+            if (ta is torch.Tensor or ta is torch.nn.Parameter) and self._eligible(a):
+                self.states.append("NY")
+                return Lazy(a, _X + ["x", "*"] * (k - 1), self, 1, (func, args, {}))
+            return _MISS
         return _MISS
 
     # ---- the state machine
@@ -507,6 +524,20 @@ class fuse(TorchFunctionMode):
         elif not info[3]:                             # not a fad operator at all: ordinary execution (NN, not logged)
             for a in args:
                 if type(a) is Lazy:
+                    if a._value is None and not info[4] and not info[5]:
+                        # YN, the common way a chain ends: a non-fad operator consumes it
+                        if kwargs:
+                            if "out" in kwargs:
+                                break
+                            for v in kwargs.values():
+                                if type(v) is Lazy:
+                                    break
+                            else:
+                                self.states.append("YN")
+                                return func(*[b.materialize() if type(b) is Lazy else b for b in args], **kwargs)
+                            break
+                        self.states.append("YN")
+                        return func(*[b.materialize() if type(b) is Lazy else b for b in args])
                     break
             else:
                 if kwargs:

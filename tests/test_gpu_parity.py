@@ -20,8 +20,10 @@ pytestmark = pytest.mark.gpu
 DTYPES = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
 DEV = "cuda:0"
 
-# sizes: several 16-byte-vector tiles plus a partial tile plus a scalar tail, for every dtype
-# (one tile = 256 lanes * unroll * 4 or 8 elements <= 8192 elements)
+# sizes: several 16-byte-vector tiles plus a partial tile plus a scalar tail, for every dtype and
+# both launch shapes (a tile is 64 or 256 vectors of 4 or 8 elements, i.e. at most 2048 elements);
+# launches that move 96 MB or more take the other shape: the full-size configuration tests, the
+# 2^32-element test and the large case of the grid-stride test cover that one
 N_RAGGED = 5 * 8192 + 3 * 256 * 8 + 777 + 3
 
 
@@ -447,7 +449,7 @@ import oracle, paper_2209_10778_amd as nfad
 from paper_2209_10778_amd import inputs
 from parity import compare
 for dtype, td in (("f32", torch.float32), ("bf16", torch.bfloat16)):
-    for n in (7 * 2048 * 5 + 333, 40 * 2048 + 1, 13):
+    for n in (7 * 2048 * 5 + 333, 40 * 2048 + 1, 13, (1 << 24) + 64 * 8 * 3 + 13):   # the last one: the large-launch shape
         a = inputs.gaussian(n, 2.0, 4242 + n)
         x = inputs.to_storage(a, dtype)
         y_ref, d_ref = oracle.fwd(nfad.MISH, inputs.storage_to_f64(x))
