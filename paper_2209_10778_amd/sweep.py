@@ -116,7 +116,8 @@ def _ints(s: str):
 def parse_args(argv=None):
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("--patterns", default="r1w2,r2w1")
-    ap.add_argument("--sizes", default="c2")
+    ap.add_argument("--sizes", default="c2", help="names of benchmark tensors (c1, c2, c3a, c3b, c3c, c4, c4h, c5) "
+                                                  "or ELEMENTS:DTYPE, e.g. 100663296:bf16")
     ap.add_argument("--threads", default="128")
     ap.add_argument("--unroll", default="2")
     ap.add_argument("--adjacent", default="0")
@@ -186,7 +187,7 @@ def main(argv=None):
     stream = torch.cuda.current_stream()
     results = []
     for size in args.sizes.split(","):
-        n, dtype = SIZES[size]
+        n, dtype = SIZES[size] if size in SIZES else (int(size.split(":")[0]), size.split(":")[1])
         td = _TD[dtype]
         es = 2 if dtype != "f32" else 4
         nbytes = n * es
