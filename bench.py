@@ -208,7 +208,7 @@ def stream_reference(bench, nfad):
     patterns = {"read_1": ("r1w0", 1), "write_1": ("r0w1", 1), "read_1_write_1": ("r1w1", 2),
                 "read_1_write_2 (pattern of nfad_fwd)": ("r1w2", 3), "read_2_write_1 (pattern of nfad_bwd)": ("r2w1", 3)}
     shapes = [dict(threads=th, unroll=u, adjacent=0, ntl=1, nts=1, waves=w, grid=0, chunk=0)
-              for th, u, w in ((64, 1, 0), (64, 1, 24), (128, 1, 24), (128, 2, 16), (128, 2, 0), (256, 2, 0),
+              for th, u, w in ((64, 1, 0), (64, 1, 21), (64, 1, 25), (128, 1, 25), (128, 2, 16), (128, 2, 0), (256, 2, 0),
                                (512, 2, 0), (512, 4, 12), (128, 4, 12))]
     fns = {}
     for label, (pat, _) in patterns.items():

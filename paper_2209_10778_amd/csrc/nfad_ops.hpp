@@ -15,7 +15,8 @@ namespace nfad {
 template <int KIND>
 struct FwdOp {
   static constexpr int kIn = 1, kOut = 2;
-  static constexpr bool kLight = KIND == kSwish;   // one exponential, one reciprocal and four more operations
+  // Swish and GELU-tanh: one exponential, one reciprocal and a handful of multiply-adds per element
+  static constexpr bool kLight = KIND == kSwish || KIND == kGeluTanh;
   template <bool kWide>
   __device__ __forceinline__ static void apply(const float (&in)[kIn], float (&out)[kOut]) {
     Act<KIND>::template eval<kWide>(in[0], out[0], out[1]);

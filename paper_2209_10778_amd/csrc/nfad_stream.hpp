@@ -53,13 +53,18 @@ static size_t max_grid() {
   return v;
 }
 
-// Dynamic-LDS bytes per block so that at most waves_per_cu waves are resident per CU.
+// Dynamic-LDS bytes per block so that at most waves_per_cu waves are resident per CU.  The
+// hardware hands out LDS in granules of 1/128 of a compute unit's LDS (1280 bytes of 160 KiB;
+// measured with blocks that only wait) and keeps floor(128 / granules per block) blocks resident,
+// so the caps that exist for one-wave blocks are 32, 25, 21, 18, 16, 14, 12, 11, ...: the
+// reservation is the smallest number of granules that admits no more than the blocks asked for.
 static unsigned lds_reservation(int waves_per_cu, int threads, int lds_per_cu) {
   const int waves_per_block = threads / 64;
   const int blocks = waves_per_cu / waves_per_block;
   if (waves_per_cu <= 0 || blocks * waves_per_block >= 32) return 0;  // 32 waves/CU is the hardware limit
-  if (blocks < 3) return 64 * 1024;                                   // 64 KiB is the per-block maximum
-  return (unsigned)((lds_per_cu / blocks) & ~1023);
+  if (blocks < 3) return 64 * 1024;                                   // the per-block maximum: two blocks stay resident
+  const int granules = 128 / (blocks + 1) + 1;                        // smallest g with floor(128 / g) <= blocks
+  return (unsigned)(granules * (lds_per_cu / 128));
 }
 
 // Grid, block and idle-LDS reservation of a launch, and which of the operation's two shapes it uses.
@@ -80,7 +85,8 @@ template <int NIN, int NOUT, typename T, bool LIGHT>
 static Geometry rule_geometry(size_t n) {
   using R = ShapeRule<NIN, NOUT, T, LIGHT>;
   constexpr int kVec = 16 / (int)sizeof(T);
-  if (R::kTwoShapes && (unsigned long long)n * sizeof(T) * (NIN + NOUT) < R::kSmallBytes)
+  const unsigned long long moved = (unsigned long long)n * sizeof(T) * (NIN + NOUT);
+  if (R::kTwoShapes && moved >= R::kSmallFromBytes && moved < R::kSmallBytes)
     return shape_geometry<typename R::Small>(n, kVec, R::kSmallWavesPerCu, true);
   return shape_geometry<typename R::Large>(n, kVec, R::kLargeWavesPerCu, false);
 }

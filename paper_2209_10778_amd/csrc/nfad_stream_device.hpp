@@ -37,11 +37,14 @@ struct Shape {
 //  * Kernels that read several tensors (backward passes) and one-read/one-write kernels run it
 //    with no cap on resident waves: best or within 1-2 % of best at every size.
 //  * Kernels that read one tensor and write several (the forward pass of the method) run it
-//    capped at 20 waves per compute unit for fp32 storage and 24 for 16-bit storage (twice the
+//    capped at 21 waves per compute unit for fp32 storage and 25 for 16-bit storage (twice the
 //    arithmetic per byte keeps a wave alive longer; an operation that declares kLight, the
-//    cheapest arithmetic, keeps 20 for 16-bit storage too).  A launch that moves less than 96 MB is
-//    over before a steady state forms, and then what counts is how fast the grid is handed
-//    out: four times fewer, fatter blocks (two waves, two accesses per lane) and no cap.
+//    cheaper arithmetic, keeps 21 for 16-bit storage too; 21 and 25 are two of the caps the LDS
+//    granule can express, see lds_reservation).  A launch that moves 9 to 48 MiB is over
+//    before a steady state forms, and then what counts is how fast the grid is handed out:
+//    four times fewer, fatter blocks (two waves, two accesses per lane) and no cap.  Below
+//    9 MiB there are too few tiles for that (the fatter blocks would leave compute units
+//    idle), and one-wave blocks win again.
 template <bool C, class A, class B>
 struct SelectType {
   using type = A;
@@ -55,10 +58,11 @@ struct ShapeRule {
   static constexpr bool kFanOut = NIN == 1 && NOUT >= 2;
   using Large = Shape<64, 1, true>;
   using Small = typename SelectType<kFanOut, Shape<128, 2, true>, Large>::type;
-  static constexpr int kLargeWavesPerCu = kFanOut ? ((sizeof(T) == 4 || LIGHT) ? 20 : 24) : 0;   // 0 = no cap
+  static constexpr int kLargeWavesPerCu = kFanOut ? ((sizeof(T) == 4 || LIGHT) ? 21 : 25) : 0;   // 0 = no cap
   static constexpr int kSmallWavesPerCu = 0;
   static constexpr bool kTwoShapes = kFanOut;
-  static constexpr unsigned long long kSmallBytes = 96ull << 20;   // bytes moved per launch
+  static constexpr unsigned long long kSmallFromBytes = 9ull << 20;   // Small shape for launches that move
+  static constexpr unsigned long long kSmallBytes = 48ull << 20;      // [kSmallFromBytes, kSmallBytes) bytes
 };
 
 // ------------------------------------------------------------------ storage formats

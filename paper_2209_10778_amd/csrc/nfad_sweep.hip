@@ -284,6 +284,25 @@ static hipError_t launch_op(int dtype, int unroll, bool ntl, const void* const* 
 }  // namespace sweep
 }  // namespace nfad
 
+// ------------------------------------------------------------------ residency probe
+// How many blocks with a given idle LDS reservation the hardware keeps resident per compute unit:
+// every block waits `ticks` ticks of the constant 100 MHz clock (bounded: at most kProbeSpins
+// polls, so the grid always drains) and then writes its index.  With R blocks resident per
+// compute unit a grid of G blocks takes ceil(G / (CUs * R)) * ticks.
+namespace nfad {
+namespace sweep {
+static constexpr int kProbeSpins = 1 << 16;
+__global__ __launch_bounds__(1024) void residency_probe_kernel(unsigned ticks, unsigned* out) {
+  const unsigned long long t0 = __builtin_amdgcn_s_memrealtime();
+  for (int spin = 0; spin < kProbeSpins; ++spin) {
+    if (__builtin_amdgcn_s_memrealtime() - t0 >= ticks) break;
+    __builtin_amdgcn_s_sleep(8);
+  }
+  if (threadIdx.x == 0) out[blockIdx.x] = blockIdx.x;
+}
+}  // namespace sweep
+}  // namespace nfad
+
 using namespace nfad;
 
 extern "C" {
@@ -425,6 +444,28 @@ int nfad_sweep_launch_phased(int pattern, int dtype, int unroll, int nt_load, in
     case NFAD_SWEEP_BWD: e = sweep::launch_phased<BwdOp>(dtype, unroll, ntl, in, out, nvec, ph, (unsigned)grid, lds, st); break;
   }
   return e == hipSuccess ? NFAD_OK : NFAD_ELAUNCH;
+}
+
+// Residency probe: `grid` blocks of `threads` threads (a multiple of 64, at most 1024), each with
+// `lds_bytes` of dynamic LDS (at most 64 KiB) it never touches, each waiting `ticks` (at most
+// 100000 = 1 ms) ticks of the 100 MHz clock before it writes its index to out[block] (device
+// memory, grid * 4 bytes).  The launch's duration tells how many blocks were resident at a time.
+int nfad_sweep_residency(int threads, unsigned lds_bytes, unsigned grid, unsigned ticks, void* out, void* stream) {
+  if (threads < 64 || threads > 1024 || threads % 64 || lds_bytes > 64u * 1024u || grid == 0 || grid > (1u << 24) ||
+      ticks > 100000u)
+    return NFAD_EINVAL_KIND;
+  if (!out) return NFAD_ENULL;
+  if ((uintptr_t)out & 3u) return NFAD_EALIGN;
+  hipLaunchKernelGGL(sweep::residency_probe_kernel, dim3(grid), dim3((unsigned)threads), lds_bytes,
+                     static_cast<hipStream_t>(stream), ticks, static_cast<unsigned*>(out));
+  return hipGetLastError() == hipSuccess ? NFAD_OK : NFAD_ELAUNCH;
+}
+
+// The idle LDS reservation libnfad's launcher makes for a cap of waves_per_cu resident waves with
+// blocks of `threads` threads on the current device (0 = no reservation).
+unsigned nfad_sweep_lds_for_cap(int waves_per_cu, int threads) {
+  if (threads < 64 || threads > 1024 || threads % 64) return 0;
+  return lds_reservation(waves_per_cu, threads, device_info().lds_per_cu);
 }
 
 }  // extern "C"

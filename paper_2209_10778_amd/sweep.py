@@ -21,6 +21,9 @@ markdown table sorted by time and, with --out, to a JSON-lines file.
 across the whole chip by the constant-rate clock (nfad_sweep_launch_phased), against the same
 kernels unphased and libnfad's own.
 
+`--residency` times blocks that only wait, with a given idle LDS reservation: how many of them
+the hardware keeps resident per compute unit, i.e. what a cap on resident waves really is.
+
 `--skew` places the tensors of a buffer set inside one allocation, 256 MiB-aligned starts plus
 k x SKEW bytes for the k-th tensor (one set of rows per value): whether the relative placement
 of the streams in memory matters.
@@ -78,6 +81,10 @@ def sweep_lib() -> ctypes.CDLL:
         L.nfad_sweep_launch.restype = ci
         L.nfad_sweep_launch_phased.argtypes = [ci, ci, ci, ci, ci, ci, ci, ci, vpp, vpp, ctypes.c_size_t, vp]
         L.nfad_sweep_launch_phased.restype = ci
+        L.nfad_sweep_residency.argtypes = [ci, ctypes.c_uint, ctypes.c_uint, ctypes.c_uint, vp, vp]
+        L.nfad_sweep_residency.restype = ci
+        L.nfad_sweep_lds_for_cap.argtypes = [ci, ci]
+        L.nfad_sweep_lds_for_cap.restype = ctypes.c_uint
         _sweep_lib = L
     return _sweep_lib
 
@@ -109,6 +116,28 @@ def launch_phased(pattern: str, dtype: str, unroll: int, waves: int, persistent:
         raise B.NfadError(rc, f"nfad_sweep_launch_phased({pattern})")
 
 
+def residency(threads: int, lds_bytes: int, per_cu: int = 1600, ticks: int = 5000, rounds: int = 3) -> float:
+    """Blocks of `threads` threads with `lds_bytes` of idle dynamic LDS that are resident per compute
+    unit at a time: `per_cu` blocks per compute unit, each waiting `ticks` x 10 ns, timed."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    grid = cus * per_cu
+    out = torch.zeros(grid, dtype=torch.int32, device="cuda:0")
+    stream = torch.cuda.current_stream()
+    best = None
+    for _ in range(rounds + 1):                      # first launch: warm-up
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        st = sweep_lib().nfad_sweep_residency(threads, lds_bytes, grid, ticks, out.data_ptr(), stream.cuda_stream)
+        if st != 0:
+            raise B.NfadError(st, "nfad_sweep_residency")
+        e1.record(stream)
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3
+        best = us if best is None else min(best, us)
+    assert bool((out == torch.arange(grid, dtype=torch.int32, device="cuda:0")).all()), "a block did not run"
+    return per_cu * ticks * 0.01 / best
+
+
 def _ints(s: str):
     return [int(v) for v in s.split(",") if v != ""]
 
@@ -123,7 +152,8 @@ def parse_args(argv=None):
     ap.add_argument("--adjacent", default="0")
     ap.add_argument("--ntl", default="0", help="nontemporal loads: 0, 1 or 0,1")
     ap.add_argument("--nts", default="1", help="nontemporal stores")
-    ap.add_argument("--waves", default="0", help="cap on resident waves per compute unit (0 = none)")
+    ap.add_argument("--waves", default="0", help="cap on resident waves per compute unit (0 = none); the hardware can express "
+                                               "32, 25, 21, 18, 16, 14, 12, 11, ... blocks: a value in between gives the next lower")
     ap.add_argument("--grid", default="0", help="0 = one block per tile; N = persistent grid of N blocks; "
                                                 "cN = N blocks per compute unit")
     ap.add_argument("--chunk", default="0", help="tiles per compute die run (0 = identity order)")
@@ -143,6 +173,10 @@ def parse_args(argv=None):
                          "--grid 0 = one block per tile / c1 = persistent; phases sized for --phase-scale x "
                          "(7.1 TB/s reads, 6.9 TB/s writes)")
     ap.add_argument("--phase-scale", default="0.9,1.0,1.1")
+    ap.add_argument("--residency", action="store_true",
+                    help="measure how many blocks of --threads threads are resident per compute unit for each idle "
+                         "LDS reservation in --lds (bytes) and for each cap in --waves as libnfad reserves for it")
+    ap.add_argument("--lds", default="", help="dynamic LDS bytes per block for --residency")
     return ap.parse_args(argv)
 
 
@@ -185,6 +219,17 @@ def main(argv=None):
     torch.cuda.set_device(dev)
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     stream = torch.cuda.current_stream()
+    if args.residency:
+        print("| threads per block | idle LDS per block, bytes | resident blocks per compute unit (two settings) | resident waves |")
+        print("|---|---|---|---|")
+        for th in _ints(args.threads):
+            cases = [(str(lds), lds) for lds in _ints(args.lds)]
+            cases += [(f"{sweep_lib().nfad_sweep_lds_for_cap(w, th)} (libnfad's reservation for a cap of {w} waves)",
+                       sweep_lib().nfad_sweep_lds_for_cap(w, th)) for w in _ints(args.waves) if w > 0]
+            for label, lds in cases:
+                r = [residency(th, lds, 1600, 5000), residency(th, lds, 800, 10000)]
+                print(f"| {th} | {label} | {r[0]:.2f} / {r[1]:.2f} | {max(r) * th / 64:.1f} |", flush=True)
+        return
     results = []
     for size in args.sizes.split(","):
         n, dtype = SIZES[size] if size in SIZES else (int(size.split(":")[0]), size.split(":")[1])

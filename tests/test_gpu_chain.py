@@ -176,6 +176,38 @@ def test_multi_output_chain_and_merged_backward(m, dtype):
     nfad.nfad_chain_release(cid)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_chain_kernels_in_their_second_block_shape(dtype):
+    """Launches that move 9 to 48 MiB take 128-thread blocks of two accesses per lane: a built-in
+    chain, a run-time compiled chain and a two-output chain at a ragged size inside that window."""
+    td = DTYPES[dtype]
+    es = 4 if dtype == "f32" else 2
+    n = (1_300_000 if dtype == "f32" else 2_600_000) + 3 * 256 * 8 + 777 + 3
+    assert 9 * 2 ** 20 <= 3 * n * es and 5 * n * es < 48 * 2 ** 20
+    x = inputs.to_storage(np.clip(inputs.gaussian(n, 2.0, 7700), -9.0, 9.0), dtype)
+    x64 = inputs.storage_to_f64(x)
+    xd = x.to(DEV)
+    builtin = [i for i, name in chains() if name == "tanhshrink"][0]
+    jit = nfad.nfad_chain_compile("x 0.25 * x tanh +")
+    for cid in (builtin, jit):
+        y, d = torch.full_like(xd, float("nan")), torch.full_like(xd, float("nan"))
+        nfad.nfad_chain_fwd(cid, xd, y, d)
+        y_ref, d_ref = chain.eval_chain(nfad.nfad_chain_program(cid), x64)
+        compare(y, y_ref, td, f"second shape chain {cid} y {dtype}", extra_tol=chain_allowance(x64, y_ref))
+        compare(d, d_ref, td, f"second shape chain {cid} dydx {dtype}", extra_tol=chain_allowance(x64, d_ref))
+    nfad.nfad_chain_release(jit)
+    programs = ["x tanh x *", "x 0.5 * softplus"]
+    cid = nfad.nfad_chain_compile_multi(programs)
+    ys = [torch.full_like(xd, float("nan")) for _ in programs]
+    ds = [torch.full_like(xd, float("nan")) for _ in programs]
+    nfad.nfad_chain_fwd_multi(cid, xd, ys, ds)
+    for j, p in enumerate(programs):
+        y_ref, d_ref = chain.eval_chain(p, x64)
+        compare(ys[j], y_ref, td, f"second shape multi y{j} {dtype}", extra_tol=chain_allowance(x64, y_ref))
+        compare(ds[j], d_ref, td, f"second shape multi d{j} {dtype}", extra_tol=chain_allowance(x64, d_ref))
+    nfad.nfad_chain_release(cid)
+
+
 def test_multi_output_autograd_front_end():
     from paper_2209_10778_amd import autograd as A
     programs = ["x tanh x *", "x tanh sigmoid"]

@@ -20,11 +20,15 @@ pytestmark = pytest.mark.gpu
 DTYPES = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
 DEV = "cuda:0"
 
-# sizes: several 16-byte-vector tiles plus a partial tile plus a scalar tail, for every dtype and
-# both launch shapes (a tile is 64 or 256 vectors of 4 or 8 elements, i.e. at most 2048 elements);
-# launches that move 96 MB or more take the other shape: the full-size configuration tests, the
-# 2^32-element test and the large case of the grid-stride test cover that one
+# sizes: several 16-byte-vector tiles plus a partial tile plus a scalar tail, for every dtype (a
+# tile is 64 or 256 vectors of 4 or 8 elements, i.e. at most 2048 elements).  Kernels with one
+# input and several outputs take a second block shape for launches that move 9 to 48 MiB:
+# n_small_shape() is a ragged size inside that window for every such kernel and storage type.
 N_RAGGED = 5 * 8192 + 3 * 256 * 8 + 777 + 3
+
+
+def n_small_shape(dtype):
+    return (1_300_000 if dtype == "f32" else 2_600_000) + 3 * 256 * 8 + 777 + 3
 
 
 def stress_x(n, seed, dtype):
@@ -66,6 +70,34 @@ def test_fwd_matches_oracle(kind, dtype):
     sy = compare(y, y_ref, td, f"fwd y kind={kind} {dtype}")
     sd = compare(d, d_ref, td, f"fwd dydx kind={kind} {dtype}")
     print(f"\n[fwd {nfad.KIND_NAMES[kind]} {dtype}] y {sy}  dydx {sd}")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_fan_out_kernels_in_their_second_block_shape(dtype):
+    """Launches that move 9 to 48 MiB: nfad_fwd and nfad_saveall_fwd in 128-thread blocks of two
+    accesses per lane -- full tiles, the ragged tile and the scalar tail of that shape."""
+    td = DTYPES[dtype]
+    n = n_small_shape(dtype)
+    es = 4 if dtype == "f32" else 2
+    for kind in nfad.KINDS:
+        x = stress_x(n, 1500 + kind, dtype)
+        x64 = inputs.storage_to_f64(x)
+        xd = dev(x)
+        assert 9 * 2 ** 20 <= 3 * n * es < 48 * 2 ** 20
+        y, d = torch.full_like(xd, float("nan")), torch.full_like(xd, float("nan"))
+        nfad.nfad_fwd(kind, xd, y, d)
+        y_ref, d_ref = oracle.fwd(kind, x64)
+        compare(y, y_ref, td, f"second shape fwd y kind={kind} {dtype}")
+        compare(d, d_ref, td, f"second shape fwd dydx kind={kind} {dtype}")
+        k = nfad.nfad_saveall_num_saved(kind)
+        assert 9 * 2 ** 20 <= (1 + k) * n * es < 48 * 2 ** 20
+        ys = torch.full_like(xd, float("nan"))
+        saved = [xd] + [torch.full_like(xd, float("nan")) for _ in range(k - 1)]
+        nfad.nfad_saveall_fwd(kind, xd, ys, saved)
+        ys_ref, saved_ref = oracle.saveall_fwd(kind, x64)
+        compare(ys, ys_ref, td, f"second shape saveall y kind={kind} {dtype}")
+        for j in range(1, k):
+            compare(saved[j], saved_ref[j], td, f"second shape saveall saved[{j}] kind={kind} {dtype}")
 
 
 @pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
@@ -449,7 +481,8 @@ import oracle, paper_2209_10778_amd as nfad
 from paper_2209_10778_amd import inputs
 from parity import compare
 for dtype, td in (("f32", torch.float32), ("bf16", torch.bfloat16)):
-    for n in (7 * 2048 * 5 + 333, 40 * 2048 + 1, 13, (1 << 24) + 64 * 8 * 3 + 13):   # the last one: the large-launch shape
+    for n in (7 * 2048 * 5 + 333, 40 * 2048 + 1, 13, 2600000 + 256 * 8 * 3 + 13,    # the last two: the second block
+              (1 << 24) + 64 * 8 * 3 + 13):                                        # shape; a long launch
         a = inputs.gaussian(n, 2.0, 4242 + n)
         x = inputs.to_storage(a, dtype)
         y_ref, d_ref = oracle.fwd(nfad.MISH, inputs.storage_to_f64(x))
