@@ -198,6 +198,31 @@ _OP_TABLE = {
 }
 
 
+def _power(e):
+    """The exponent of a power the primitives can spell: an integer 2..8 (also written as a float),
+    0.5, -1 or -0.5; None for any other."""
+    if isinstance(e, bool) or not isinstance(e, (int, float)):
+        return None
+    if e in (0.5, -1, -0.5):
+        return float(e)
+    if float(e).is_integer() and 2 <= e <= 8:
+        return int(e)
+    return None
+
+
+def _pow_program(a, k):
+    if k == 0.5:
+        return a + ["sqrt"]
+    if k == -1.0:
+        return ["1"] + a + ["/"]
+    if k == -0.5:
+        return ["1"] + a + ["sqrt", "/"]
+    prog = list(a)
+    for _ in range(k - 1):
+        prog = prog + a + ["*"]
+    return prog
+
+
 def _op_name(func):
     return _OP_TABLE.get(getattr(func, "__name__", ""))
 
@@ -370,13 +395,11 @@ class fuse(TorchFunctionMode):
                     if hi is not None:
                         prog += [_const(hi), "min"]
         elif op == "pow":
-            if len(args) == 2 and not kwargs and isinstance(args[1], int) and not isinstance(args[1], bool) \
-                    and 2 <= args[1] <= 8:
+            k = _power(args[1]) if len(args) == 2 and not kwargs else None
+            if k is not None:
                 a = self._operand(args[0], source)
                 if a is not None:
-                    prog = list(a)
-                    for _ in range(args[1] - 1):
-                        prog = prog + a + ["*"]
+                    prog = _pow_program(a, k)
         elif op in _UNARY:
             if len(args) == 1 and (not kwargs or kwargs == {"inplace": False}):
                 a = self._operand(args[0], source)
@@ -459,20 +482,23 @@ class fuse(TorchFunctionMode):
                     nops += o._nops
             self.states.append("YY" if lazy_in else "NY")
             return Lazy(source, prog, self, nops, None if lazy_in else (func, args, {}))
-        if kind == 3:                                 # a small integer power: repeated multiplication
-            if len(args) != 2 or type(args[1]) is not int or not 2 <= args[1] <= 8:
+        if kind == 3:                                 # a power the primitives can spell
+            if len(args) != 2:
                 return _MISS
-            a, k = args
+            k = _power(args[1])
+            if k is None:
+                return _MISS
+            a = args[0]
             ta = type(a)
             if ta is Lazy:
-                if a._value is not None or len(a._program) * k + k > 250:
+                if a._value is not None or len(a._program) * 8 + 8 > 250:
                     return _MISS
                 a._extended = True
                 self.states.append("YY")
-                return Lazy(a._source, a._program + (a._program + ["*"]) * (k - 1), self, a._nops + 1, None)
+                return Lazy(a._source, _pow_program(a._program, k), self, a._nops + 1, None)
             if (ta is torch.Tensor or ta is torch.nn.Parameter) and self._eligible(a):
                 self.states.append("NY")
-                return Lazy(a, _X + ["x", "*"] * (k - 1), self, 1, (func, args, {}))
+                return Lazy(a, _pow_program(_X, k), self, 1, (func, args, {}))
             return _MISS
         return _MISS
 

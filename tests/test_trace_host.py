@@ -123,7 +123,8 @@ def test_unsupported_variants_do_not_start_a_chain():
         assert not isinstance(torch.tanh(xi.double()), trace.Lazy)      # float64 is not a storage type here
         assert not isinstance(x ** 2.5, trace.Lazy)
         assert not isinstance(x + torch.randn(1), trace.Lazy)           # broadcasting a different tensor
-        assert isinstance(x ** 2, trace.Lazy)
+        assert not isinstance(x ** 9, trace.Lazy) and not isinstance(x ** True, trace.Lazy)
+        assert isinstance(x ** 2, trace.Lazy) and isinstance(torch.pow(x, 3.0), trace.Lazy)
 
 
 FUNCTIONALS = {
@@ -147,6 +148,12 @@ FUNCTIONALS = {
     "elu": (lambda t: F.elu(t, alpha=1.3), False),
     "hardswish": (F.hardswish, False),
     "relu6": (F.relu6, False),
+    "pow_float_3": (lambda t: torch.pow(t, 3.0), False),
+    "pow_int_4": (lambda t: t ** 4, False),
+    "pow_half": (lambda t: t ** 0.5, True),
+    "pow_minus_one": (lambda t: torch.pow(t, -1), True),
+    "pow_minus_half": (lambda t: t.pow(-0.5), True),
+    "pow_of_a_chain": (lambda t: torch.pow(torch.tanh(t), 2.0), False),
 }
 
 
