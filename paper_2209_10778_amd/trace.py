@@ -136,10 +136,14 @@ def _flatten(xs):
     return out
 
 
+_F32_MAX = 3.4028234663852886e38
+
+
 def _const(v) -> Optional[str]:
+    """A Python number as a program token; None for anything else, for NaN and for magnitudes fp32 cannot hold."""
     if isinstance(v, bool) or not isinstance(v, (int, float)):
         return None
-    return repr(float(v)) if math.isfinite(float(v)) else None
+    return repr(float(v)) if -_F32_MAX <= v <= _F32_MAX else None
 
 
 # fad operators: name -> (arity, builder over operand programs)
@@ -460,7 +464,7 @@ class fuse(TorchFunctionMode):
                         return _MISS
                     source = o
                     progs.append(_X)
-                elif (to is float or to is int) and o == o and o not in (math.inf, -math.inf):
+                elif (to is float or to is int) and -_F32_MAX <= o <= _F32_MAX:
                     progs.append([repr(float(o))])
                 else:
                     return _MISS

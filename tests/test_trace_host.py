@@ -257,3 +257,16 @@ def test_chains_over_one_source_waiting_to_be_consumed_are_resolved_together(int
     assert t.kernels == ["x tanh x * ; x tanh sigmoid", "x neg exp x *"]
     assert torch.allclose(sa, (torch.tanh(x) * x).sum()) and torch.allclose(sb, torch.sigmoid(torch.tanh(x)).sum())
     assert torch.allclose(sc, (torch.exp(-x) * x).sum())
+
+
+def test_numbers_fp32_cannot_hold_do_not_enter_a_chain():
+    x = torch.randn(6)
+    with trace.fuse(require_cuda=False):
+        for c in (float("nan"), float("inf"), 1e39, -1e39):
+            assert not isinstance(x * c, trace.Lazy)
+        assert not isinstance(torch.clamp(x, max=float("inf")), trace.Lazy)
+        with pytest.raises(OverflowError):
+            x * 10 ** 400                     # what the framework itself does with such a number
+        ok = x * 3.0e38
+        assert isinstance(ok, trace.Lazy)
+        ok._value = x                         # nothing to resolve on leaving the context
