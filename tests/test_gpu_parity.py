@@ -84,11 +84,16 @@ def test_fan_out_kernels_in_their_second_block_shape(dtype):
         x64 = inputs.storage_to_f64(x)
         xd = dev(x)
         assert 9 * 2 ** 20 <= 3 * n * es < 48 * 2 ** 20
-        y, d = torch.full_like(xd, float("nan")), torch.full_like(xd, float("nan"))
+        pad = 64                                        # canaries either side; keeps the views 16-byte aligned
+        by = torch.full((n + 2 * pad,), 777.0, dtype=td, device=DEV)
+        bd = torch.full((n + 2 * pad,), 777.0, dtype=td, device=DEV)
+        y, d = by[pad:pad + n], bd[pad:pad + n]
         nfad.nfad_fwd(kind, xd, y, d)
         y_ref, d_ref = oracle.fwd(kind, x64)
         compare(y, y_ref, td, f"second shape fwd y kind={kind} {dtype}")
         compare(d, d_ref, td, f"second shape fwd dydx kind={kind} {dtype}")
+        for b in (by, bd):
+            assert bool((b[:pad] == 777.0).all()) and bool((b[pad + n:] == 777.0).all()), "wrote out of bounds"
         k = nfad.nfad_saveall_num_saved(kind)
         assert 9 * 2 ** 20 <= (1 + k) * n * es < 48 * 2 ** 20
         ys = torch.full_like(xd, float("nan"))
